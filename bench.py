@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Throughput of one pipeline stage's micro-batched training step on one MI355X.
+
+A step is one mini-batch on the stage: grad_accum_reset, M forwards (boundary
+activation kept only), then M recompute+backward calls with fp32 gradient
+accumulation -- all through the C ABI, inputs resident in HBM before timing.
+Prints ONE JSON line (metric, value, roofline of the dominant kernel measured
+with HIP events, and the fp64 oracle timed on the host cores as cpu_baseline).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="C5", help="C1..C5 (default: the largest stage, C5)")
+    ap.add_argument("--micro-batches", type=int, default=0, help="override M (default: the config's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-profile", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg):
+    """The fp64 oracle as it stands, on a bounded sample of the same workload:
+    one layer, one micro-batch, sequence shortened so it costs ~10-30 s."""
+    import numpy as np
+    from oracle import stage_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    h, f = cfg.hidden, cfg.mlp_hidden
+    budget = 1.0e12  # FLOPs of fp64 work to aim for
+    per_token = 3.0 * 2.0 * h * (4 * h + 2 * f)
+    s = cfg.seq_len
+    while s > 64 and per_token * s * cfg.micro_batch > budget:
+        s //= 2
+    b = cfg.micro_batch
+    while b > 1 and per_token * s * b > budget:
+        b //= 2
+    sh = O.StageShape(1, h, cfg.n_heads, s, b, f, cfg.causal, cfg.ln_eps)
+    rng = np.random.default_rng(cfg.seed)
+    p = {k: rng.standard_normal(shp) * cfg.w_std for k, shp in O.param_shapes(sh).items()}
+    p["ln1_g"] += 1.0
+    p["ln2_g"] += 1.0
+    x = rng.standard_normal((sh.tokens, h))
+    dy = rng.standard_normal((sh.tokens, h))
+    t0 = time.perf_counter()
+    y, caches = O.stage_forward(x, [p], sh)
+    O.stage_backward(dy, [p], caches, sh)
+    dt = time.perf_counter() - t0
+    attn = 4.0 * sh.tokens * s * h * (0.5 if cfg.causal else 1.0)
+    useful = 3.0 * (2.0 * sh.tokens * h * (4 * h + 2 * f) + attn)
+    return {
+        "value": useful / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"fp64 numpy oracle, 1 layer of {cfg.name}, micro-batch {b} x seq {s} "
+                  f"(of {cfg.micro_batch} x {cfg.seq_len}), forward+backward = 3 forward units, "
+                  f"{dt:.1f} s wall",
+        "seconds": dt, "host_cpus": os.cpu_count(),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the stage step; this build has no multi-GPU path "
+              "(run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2111_04007_amd import CONFIGS, binding as B, flops, synth
+
+    cfg = CONFIGS[args.config]
+    if args.micro_batches:
+        cfg = cfg.replace(n_micro_batches=args.micro_batches)
+    M = cfg.n_micro_batches
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    props = torch.cuda.get_device_properties(dev)
+
+    params, xs, dys = synth.device_random_stage(cfg, dev)
+    st = B.Stage(cfg, dev, params_flat=params)
+    ys = torch.empty_like(xs)
+    dxs = torch.empty_like(xs)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        st.grad_accum_reset(stream)
+        for m in range(M):
+            st.forward(m, xs[m], ys[m], stream)
+        for m in range(M):
+            st.backward_recompute(m, dys[m], dxs[m], stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    ms_mb = ms_step / M
+
+    # separate forward / recompute+backward timing with events on the same stream
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    st.grad_accum_reset(stream)
+    ev[0].record(stream)
+    for m in range(M):
+        st.forward(m, xs[m], ys[m], stream)
+    ev[1].record(stream)
+    for m in range(M):
+        st.backward_recompute(m, dys[m], dxs[m], stream)
+    ev[2].record(stream)
+    torch.cuda.synchronize()
+    ms_f = ev[0].elapsed_time(ev[1]) / M
+    ms_rb = ev[1].elapsed_time(ev[2]) / M
+
+    # FLOP accounting: 4 forward units per micro-batch (causal-aware), minus the last
+    # layer's MLP2 GEMM that the recompute pass does not need and does not run.
+    skipped = 2.0 * cfg.tokens * cfg.hidden * cfg.mlp_hidden
+    hw_flops_mb = flops.step_flops_per_microbatch(cfg) - skipped
+    useful_flops_mb = flops.useful_flops_per_microbatch(cfg)
+    tflops = hw_flops_mb * M / (ms_step * 1e-3) / 1e12
+    frac_peak = tflops * 1e12 / flops.MI355X_BF16_DENSE_PEAK
+
+    roofline = None
+    classes = None
+    if not args.no_kernel_profile:
+        st.profile_enable(True)
+        tot = {}
+        for _ in range(args.steps):
+            st.grad_accum_reset(stream)
+            for m in range(M):
+                st.forward(m, xs[m], ys[m], stream)
+                if m % 8 == 7 or m == M - 1:
+                    _acc(tot, st.profile_collect())
+            for m in range(M):
+                st.backward_recompute(m, dys[m], dxs[m], stream)
+                _acc(tot, st.profile_collect())
+        st.profile_enable(False)
+        classes = {k: {"ms_per_step": v["ms"] / args.steps, "launches_per_step": v["launches"] // args.steps,
+                       "tflops": (v["flops"] / (v["ms"] * 1e-3) / 1e12) if v["ms"] > 0 and v["flops"] > 0 else None,
+                       "gbps": (v["bytes"] / (v["ms"] * 1e-3) / 1e9) if v["ms"] > 0 else None}
+                   for k, v in tot.items() if v["launches"]}
+        dom = max(tot.items(), key=lambda kv: kv[1]["ms"])
+        name, v = dom
+        if v["flops"] > 0:
+            is_f32 = cfg.dtype == "f32"
+            peak = 157.3 if is_f32 else flops.MI355X_BF16_DENSE_PEAK / 1e12
+            ach = v["flops"] / (v["ms"] * 1e-3) / 1e12
+            roofline = {"kernel": name, "bound": "alu" if is_f32 else "mfma", "achieved": ach, "peak": peak,
+                        "unit": "TFLOP/s", "frac": ach / peak, "traffic": None,
+                        "avg_launch_ms": v["ms"] / v["launches"], "launches": v["launches"] // args.steps}
+        else:
+            ach = v["bytes"] / (v["ms"] * 1e-3) / 1e9
+            roofline = {"kernel": name, "bound": "hbm", "achieved": ach, "peak": flops.MI355X_HBM_PEAK / 1e9,
+                        "unit": "GB/s", "frac": ach / (flops.MI355X_HBM_PEAK / 1e9), "traffic": None,
+                        "avg_launch_ms": v["ms"] / v["launches"], "launches": v["launches"] // args.steps}
+
+    cpu = None if args.no_cpu_baseline else cpu_baseline(cfg)
+
+    out = {
+        "metric": "stage fwd+recompute+bwd TFLOP/s (ms/micro-batch and % of bf16 MFMA peak in config)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {
+            "workload": cfg.name, "n_layers": cfg.n_layers, "hidden": cfg.hidden, "n_heads": cfg.n_heads,
+            "seq_len": cfg.seq_len, "micro_batch": cfg.micro_batch, "n_micro_batches": M,
+            "mlp_hidden": cfg.mlp_hidden, "causal": cfg.causal,
+            "ms_per_micro_batch": ms_mb, "ms_forward_per_micro_batch": ms_f,
+            "ms_recompute_backward_per_micro_batch": ms_rb,
+            "frac_of_bf16_mfma_peak": frac_peak, "peak_tflops_used": flops.MI355X_BF16_DENSE_PEAK / 1e12,
+            "useful_tflops_paper_convention": useful_flops_mb * M / (ms_step * 1e-3) / 1e12,
+            "flops_per_micro_batch_executed": hw_flops_mb,
+            "device": props.name, "compute_units": props.multi_processor_count,
+            "kernel_classes": classes,
+        },
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    st.close()
+    print(json.dumps(out))
+
+
+def _acc(tot, part):
+    for k, v in part.items():
+        t = tot.setdefault(k, {"ms": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0})
+        for kk in t:
+            t[kk] += v[kk]
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,211 @@
+/*
+ * varuna_stage.h -- C ABI of the MI355X (gfx950) pipeline-stage compute library.
+ *
+ * One pipeline stage's micro-batched training step for a GPT-style transformer:
+ * forward for each micro-batch keeping only the stage-input ("boundary")
+ * activation; backward first recomputes the stage's internal activations from
+ * that stored tensor, then produces the input gradient and the parameter
+ * gradients, which accumulate in fp32 over the micro-batches a GPU holds.
+ * (Paper: Design Overview, "High-level architecture" -- stage k takes
+ * activations from k-1 and gradients from k+1, and recomputes activations from
+ * the stored input activation; Background, "Memory optimization" -- gradient
+ * checkpointing, forward is about a third of the compute; Job Morphing,
+ * "Correctness-preserving morphing" -- gradient accumulation within a GPU.)
+ *
+ * Conventions
+ *   - Every pointer marked "device" is GPU memory owned by the caller (the
+ *     caller allocates, e.g. through PyTorch); it must stay valid until
+ *     varuna_stage_destroy and be 256-byte aligned.  The library allocates no
+ *     device memory in any call.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     Every compute call only enqueues work on it and returns; nothing
+ *     synchronises with the host.  One handle is used from one stream at a time.
+ *   - Activations are row-major [T, h], T = micro_batch * seq_len, row index
+ *     = batch_index * seq_len + position.  dtype F32: all tensors fp32.
+ *     dtype BF16: activations, parameters and dX are bf16; all accumulators,
+ *     LayerNorm statistics, log-sum-exp and every parameter gradient are fp32.
+ *   - Parameter buffer layout: layers back to back; inside a layer, in this
+ *     order, each matrix row-major [out, in]:
+ *        ln1_g[h] ln1_b[h] Wqkv[3h,h] bqkv[3h] Wo[h,h] bo[h]
+ *        ln2_g[h] ln2_b[h] W1[f,h] b1[f] W2[h,f] b2[h]
+ *     Rows of Wqkv are [Q | K | V] blocks of h rows; head j owns rows
+ *     j*d .. (j+1)*d-1 of each block (d = h / heads).  The gradient buffer has
+ *     the same element order, always fp32.  varuna_stage_param_offset reports
+ *     the element offsets.
+ *   - Every call returns a varuna_status_t; on failure varuna_last_error()
+ *     returns a message (thread-local storage, valid until the next failing
+ *     call on that thread).  Argument checks never touch the GPU.
+ */
+#ifndef VARUNA_STAGE_H
+#define VARUNA_STAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct varuna_stage varuna_stage_t; /* opaque, host memory owned by the library */
+
+typedef enum {
+  VARUNA_OK = 0,
+  VARUNA_EINVAL = -1,       /* bad argument or configuration */
+  VARUNA_ESTATE = -2,       /* call order violated (e.g. backward before forward of that slot) */
+  VARUNA_ENOMEM = -3,       /* host allocation failed */
+  VARUNA_EHIP = -4,         /* a HIP runtime call or kernel launch failed */
+  VARUNA_EUNSUPPORTED = -5  /* valid but not implemented for this shape */
+} varuna_status_t;
+
+typedef enum { VARUNA_F32 = 0, VARUNA_BF16 = 1 } varuna_dtype_t;
+
+/* Number of parameter tensors per layer and their indices in the layout above. */
+#define VARUNA_PARAMS_PER_LAYER 12
+enum {
+  VARUNA_P_LN1_G = 0, VARUNA_P_LN1_B, VARUNA_P_WQKV, VARUNA_P_BQKV, VARUNA_P_WO, VARUNA_P_BO,
+  VARUNA_P_LN2_G, VARUNA_P_LN2_B, VARUNA_P_W1, VARUNA_P_B1, VARUNA_P_W2, VARUNA_P_B2
+};
+
+/* Plain data; the library copies it. */
+typedef struct {
+  int32_t n_layers;        /* L >= 1: transformer layers in this stage */
+  int32_t hidden;          /* h */
+  int32_t n_heads;         /* a, must divide h */
+  int32_t seq_len;         /* s */
+  int32_t micro_batch;     /* b: examples per micro-batch (the paper's m) */
+  int32_t n_micro_batches; /* M: number of boundary slots (the paper's N_m) */
+  int32_t mlp_hidden;      /* f; 0 means 4*h */
+  int32_t causal;          /* 1: key index <= query index only; 0: bidirectional */
+  int32_t dtype;           /* varuna_dtype_t */
+  float ln_eps;            /* 0 means 1e-5 */
+} varuna_stage_config_t;
+
+/* Byte sizes of the four caller-allocated device buffers for this configuration.
+ * boundary_bytes = M * T * h * sizeof(activation): one stage-input tensor per
+ * micro-batch is all that forward keeps (Design Overview: 3.75 MB per example
+ * for h=1920, s=1024 in 16-bit).  Any output pointer may be NULL. */
+varuna_status_t varuna_stage_query_sizes(const varuna_stage_config_t* cfg, size_t* param_bytes,
+                                         size_t* grad_bytes, size_t* boundary_bytes,
+                                         size_t* workspace_bytes);
+
+/* Element offset (from the start of the parameter buffer, equally of the
+ * gradient buffer) and element count of parameter tensor `which` of `layer`. */
+varuna_status_t varuna_stage_param_offset(const varuna_stage_config_t* cfg, int32_t layer,
+                                          int32_t which, size_t* offset_elems, size_t* n_elems);
+
+/* Creates a stage over caller-owned device buffers of the sizes reported by
+ * varuna_stage_query_sizes.  params: read-only; grads_f32: accumulators, not
+ * cleared here (call varuna_stage_grad_accum_reset); boundary: M slots [T,h];
+ * workspace: scratch, contents undefined between calls.  Validates the
+ * configuration without touching the GPU. */
+varuna_status_t varuna_stage_create(const varuna_stage_config_t* cfg, const void* params /*device*/,
+                                    void* grads_f32 /*device*/, void* boundary /*device*/,
+                                    void* workspace /*device*/, varuna_stage_t** out);
+
+/* Stage forward for micro-batch slot mb (0 <= mb < M): copies x_in [T,h] into
+ * boundary slot mb (skipped when x_in is that slot), runs the L layers, writes
+ * the stage output y_out [T,h].  Nothing else is kept. */
+varuna_status_t varuna_stage_forward(varuna_stage_t* st, int32_t mb, const void* x_in /*device*/,
+                                     void* y_out /*device*/, void* hip_stream);
+
+/* Recompute + backward for slot mb: re-derives all internal activations from
+ * boundary slot mb (bit-identical to what forward computed), then from the
+ * upstream gradient dy_in [T,h] writes the input gradient dx_out [T,h] and adds
+ * this micro-batch's parameter gradients into grads_f32.  Requires a forward of
+ * slot mb since that slot was last consumed (else VARUNA_ESTATE).  Calls for
+ * different slots may be interleaved with forwards in any order. */
+varuna_status_t varuna_stage_backward_recompute(varuna_stage_t* st, int32_t mb,
+                                                const void* dy_in /*device*/,
+                                                void* dx_out /*device*/, void* hip_stream);
+
+/* Zero-fills grads_f32 (start of a mini-batch). */
+varuna_status_t varuna_stage_grad_accum_reset(varuna_stage_t* st, void* hip_stream);
+
+/* Releases the host-side handle.  Device buffers stay with the caller. */
+varuna_status_t varuna_stage_destroy(varuna_stage_t* st);
+
+const char* varuna_last_error(void);
+
+/* ---- test hooks (not on the timed path) -------------------------------- */
+
+/* Forward that also stores the internal activations of every layer in the
+ * workspace, exactly as the recompute pass stores them, so a test can compare
+ * the two bit for bit. */
+varuna_status_t varuna_stage_debug_forward_save(varuna_stage_t* st, int32_t mb,
+                                                const void* x_in /*device*/,
+                                                void* y_out /*device*/, void* hip_stream);
+/* Byte range of the workspace that holds those stored activations. */
+varuna_status_t varuna_stage_debug_saved_region(const varuna_stage_t* st, size_t* offset_bytes,
+                                                size_t* n_bytes);
+
+/* ---- per-kernel timing (HIP events on the caller's stream) -------------- */
+
+/* Kernel classes reported by the profiler. */
+enum {
+  VARUNA_K_GEMM_FWD = 0,  /* Y = X W^T (+bias, GeLU, residual) */
+  VARUNA_K_GEMM_DGRAD,    /* dX = dY W (+GeLU') */
+  VARUNA_K_GEMM_WGRAD,    /* dW += dY^T X */
+  VARUNA_K_ATTN_FWD,
+  VARUNA_K_ATTN_BWD,
+  VARUNA_K_LN_FWD,
+  VARUNA_K_LN_BWD,
+  VARUNA_K_COLREDUCE,     /* bias / gamma / beta gradient reductions */
+  VARUNA_K_OTHER,         /* copies, fills */
+  VARUNA_K_COUNT
+};
+/* While enabled, each kernel launch is bracketed by HIP events on the stream it
+ * runs on.  Events come from a fixed pool created here (no device memory). */
+varuna_status_t varuna_stage_profile_enable(varuna_stage_t* st, int32_t on);
+/* Synchronises the recorded events, adds their durations per class into
+ * ms[VARUNA_K_COUNT], launches[...] and flops[...] (algorithmic FLOPs of the
+ * launches, 0 for memory-bound classes) and bytes[...] (algorithmic HBM bytes),
+ * then clears the record. */
+varuna_status_t varuna_stage_profile_collect(varuna_stage_t* st, double* ms, int64_t* launches,
+                                             double* flops, double* bytes);
+
+/* ---- single-operation entry points (unit parity tests, kernel tuning) ---- */
+
+/* C[M,N] = A * B^T style products on device buffers, dtype as varuna_dtype_t.
+ * op: 0 forward  (a = X[M,K],  b = W[N,K],  out[M,N]  = X W^T + bias; epi selects
+ *                 0 bias, 1 bias+GeLU (aux_out receives pre-GeLU u if not NULL),
+ *                 2 bias+residual (aux_in = residual [M,N]))
+ *     1 dgrad    (a = dY[M,K], b = W[K,N],  out[M,N]  = dY W; epi 0 plain,
+ *                 3 multiply by GeLU'(aux_in[M,N]))
+ *     2 wgrad    (a = dY[K,M], b = X[K,N],  out_f32[M,N] += dY^T X)
+ * variant: 0 = library's choice; other values force one kernel configuration
+ * (VARUNA_EUNSUPPORTED if it cannot run the shape). */
+varuna_status_t varuna_op_gemm(int32_t dtype, int32_t op, int32_t epi, int32_t variant, int64_t M,
+                               int64_t N, int64_t K, const void* a, const void* b,
+                               const void* bias, const void* aux_in, void* out, void* aux_out,
+                               void* hip_stream);
+
+/* LayerNorm forward: y = gamma*(x-mean)*rstd+beta on [rows, h]; stats_f32
+ * ([2*rows]: mean then rstd) may be NULL. */
+varuna_status_t varuna_op_layernorm_fwd(int32_t dtype, int64_t rows, int64_t h, float eps,
+                                        const void* x, const void* gamma, const void* beta,
+                                        void* y, float* stats_f32, void* hip_stream);
+/* LayerNorm backward: dx = res + LN'(dy); dgamma_f32, dbeta_f32 [h] are added to.
+ * partial_f32 is scratch of at least varuna_op_colreduce_scratch_bytes(rows, 2*h). */
+varuna_status_t varuna_op_layernorm_bwd(int32_t dtype, int64_t rows, int64_t h, const void* dy,
+                                        const void* x, const float* stats_f32, const void* gamma,
+                                        const void* res, void* dx, float* dgamma_f32,
+                                        float* dbeta_f32, float* partial_f32, void* hip_stream);
+/* out_f32[n] += sum over rows of a[rows, n]. */
+varuna_status_t varuna_op_colsum(int32_t dtype, int64_t rows, int64_t n, const void* a,
+                                 float* out_f32, float* partial_f32, void* hip_stream);
+size_t varuna_op_colreduce_scratch_bytes(int64_t rows, int64_t n);
+
+/* Attention forward on qkv [b*s, 3h] -> ctx [b*s, h], lse_f32 [b, heads, s]. */
+varuna_status_t varuna_op_attention_fwd(int32_t dtype, int32_t variant, int32_t b, int32_t s,
+                                        int32_t heads, int32_t d, int32_t causal, const void* qkv,
+                                        void* ctx, float* lse_f32, void* hip_stream);
+/* Attention backward: dqkv [b*s, 3h] from dctx; delta_f32 [b, heads, s] scratch. */
+varuna_status_t varuna_op_attention_bwd(int32_t dtype, int32_t variant, int32_t b, int32_t s,
+                                        int32_t heads, int32_t d, int32_t causal, const void* qkv,
+                                        const void* ctx, const float* lse_f32, const void* dctx,
+                                        void* dqkv, float* delta_f32, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VARUNA_STAGE_H */

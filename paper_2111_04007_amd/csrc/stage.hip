@@ -1,0 +1,684 @@
+// Stage driver and C ABI (see include/varuna_stage.h for the contract).
+//
+// Host side only enqueues kernels on the caller's stream.  The layer loop:
+//   forward   : LN1 -> QKV GEMM(+bias) -> attention -> proj GEMM(+bias+residual)
+//               -> LN2 -> MLP1 GEMM(+bias+GeLU) -> MLP2 GEMM(+bias+residual)
+//   recompute : the same launches, additionally storing LN statistics, the
+//               log-sum-exp and the pre-GeLU values, each layer into its own
+//               region of the workspace (the last layer's MLP2 is not needed by
+//               the backward pass and is skipped)
+//   backward  : per layer, top down: MLP2 dgrad(+GeLU') / wgrad, MLP1 dgrad /
+//               wgrad, LN2 backward, proj dgrad / wgrad, attention backward,
+//               QKV dgrad / wgrad, LN1 backward; bias / gamma / beta gradients by
+//               two-stage column reductions.  Every parameter gradient is added
+//               to the caller's fp32 buffer.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/varuna_stage.h"
+#include "attention_mfma.h"
+#include "attention_simple.h"
+#include "common.h"
+#include "gemm_mfma.h"
+#include "gemm_simple.h"
+#include "norm_reduce.h"
+
+using namespace varuna;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+varuna_status_t fail(varuna_status_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                          \
+  do {                                                                                         \
+    hipError_t e_ = (expr);                                                                    \
+    if (e_ != hipSuccess)                                                                      \
+      return fail(VARUNA_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+struct Dims {
+  int L, h, a, d, s, b, M, f, causal, dtype;
+  float eps;
+  int64_t T, E, F;  // tokens, T*h, T*f
+  size_t es;        // bytes per activation / parameter element
+};
+
+varuna_status_t make_dims(const varuna_stage_config_t* c, Dims* o) {
+  if (!c) return fail(VARUNA_EINVAL, "config is NULL");
+  if (c->n_layers < 1 || c->hidden < 1 || c->n_heads < 1 || c->seq_len < 1 || c->micro_batch < 1 ||
+      c->n_micro_batches < 1 || c->mlp_hidden < 0)
+    return fail(VARUNA_EINVAL, "non-positive dimension in config");
+  if (c->hidden % c->n_heads != 0)
+    return fail(VARUNA_EINVAL, "hidden (%d) is not a multiple of n_heads (%d)", c->hidden, c->n_heads);
+  if (c->dtype != VARUNA_F32 && c->dtype != VARUNA_BF16) return fail(VARUNA_EINVAL, "unknown dtype %d", c->dtype);
+  if (c->causal != 0 && c->causal != 1) return fail(VARUNA_EINVAL, "causal must be 0 or 1");
+  if (!(c->ln_eps >= 0.0f)) return fail(VARUNA_EINVAL, "ln_eps must be >= 0");
+  o->L = c->n_layers; o->h = c->hidden; o->a = c->n_heads; o->d = c->hidden / c->n_heads;
+  o->s = c->seq_len; o->b = c->micro_batch; o->M = c->n_micro_batches;
+  o->f = c->mlp_hidden ? c->mlp_hidden : 4 * c->hidden;
+  o->causal = c->causal; o->dtype = c->dtype;
+  o->eps = c->ln_eps > 0.0f ? c->ln_eps : 1e-5f;
+  o->T = (int64_t)o->b * o->s; o->E = o->T * o->h; o->F = o->T * o->f;
+  o->es = c->dtype == VARUNA_F32 ? 4 : 2;
+  if (o->s > ATS_MAX_S) return fail(VARUNA_EUNSUPPORTED, "seq_len %d exceeds the supported maximum %d", o->s, ATS_MAX_S);
+  if (o->d > ATS_MAX_D) return fail(VARUNA_EUNSUPPORTED, "head dim %d exceeds the supported maximum %d", o->d, ATS_MAX_D);
+  if (o->T > (1ll << 24) || (int64_t)o->h > (1 << 20) || (int64_t)o->f > (1 << 22))
+    return fail(VARUNA_EUNSUPPORTED, "dimension too large");
+  return VARUNA_OK;
+}
+
+// element offsets of the 12 parameter tensors inside one layer
+struct ParamOffsets { size_t off[VARUNA_PARAMS_PER_LAYER]; size_t n[VARUNA_PARAMS_PER_LAYER]; size_t per_layer; };
+ParamOffsets param_offsets(const Dims& D) {
+  const size_t h = D.h, f = D.f;
+  const size_t n[VARUNA_PARAMS_PER_LAYER] = {h, h, 3 * h * h, 3 * h, h * h, h, h, h, f * h, f, h * f, h};
+  ParamOffsets p;
+  size_t o = 0;
+  for (int i = 0; i < VARUNA_PARAMS_PER_LAYER; ++i) { p.off[i] = o; p.n[i] = n[i]; o += n[i]; }
+  p.per_layer = o;
+  return p;
+}
+
+// byte offsets inside the workspace
+struct LayerArea { size_t stats1, xn1, qkv, lse, ctx, x1, stats2, xn2, u, g, y, end; };
+struct Workspace {
+  std::vector<LayerArea> layer;  // saved activations, one area per layer
+  size_t saved_begin, saved_end;
+  size_t ping[2];                // forward layer outputs (discarded)
+  size_t dping[2], du, dxn, dx1, dctx, dqkv, delta, partial;
+  size_t total;
+};
+Workspace carve(const Dims& D) {
+  Workspace w;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes); return r; };
+  const size_t E = (size_t)D.E * D.es, F = (size_t)D.F * D.es;
+  const size_t lse = (size_t)D.b * D.a * D.s * sizeof(float), st = (size_t)2 * D.T * sizeof(float);
+  w.saved_begin = o;
+  for (int l = 0; l < D.L; ++l) {
+    LayerArea a;
+    a.stats1 = take(st); a.xn1 = take(E); a.qkv = take(3 * E); a.lse = take(lse); a.ctx = take(E);
+    a.x1 = take(E); a.stats2 = take(st); a.xn2 = take(E); a.u = take(F); a.g = take(F); a.y = take(E);
+    a.end = o;
+    w.layer.push_back(a);
+  }
+  w.saved_end = o;
+  w.ping[0] = take(E); w.ping[1] = take(E);
+  w.dping[0] = take(E); w.dping[1] = take(E);
+  w.du = take(F); w.dxn = take(E); w.dx1 = take(E); w.dctx = take(E); w.dqkv = take(3 * E);
+  w.delta = take(lse);
+  int64_t widest = 3 * (int64_t)D.h;
+  if (D.f > widest) widest = D.f;
+  w.partial = take((size_t)colreduce_chunks(D.T) * widest * sizeof(float));
+  w.total = o;
+  return w;
+}
+
+constexpr int kMaxEvents = 4096;
+
+}  // namespace
+
+struct varuna_stage {
+  Dims D;
+  ParamOffsets po;
+  Workspace ws;
+  const char* params;
+  float* grads;
+  char* boundary;
+  char* work;
+  std::vector<char> forwarded;
+  // profiler
+  bool prof_on = false;
+  std::vector<hipEvent_t> ev;  // pairs
+  struct Rec { int cls; double flops, bytes; };
+  std::vector<Rec> recs;
+};
+
+namespace {
+
+__global__ void fill_zero_f32_kernel(float* p, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = 0.f;
+}
+
+// RAII-free profiling bracket: records start/stop events around one launch group.
+struct Bracket {
+  varuna_stage* st; hipStream_t s; bool active;
+  Bracket(varuna_stage* st_, hipStream_t s_, int cls, double flops, double bytes) : st(st_), s(s_), active(false) {
+    if (st && st->prof_on && st->recs.size() * 2 + 2 <= st->ev.size()) {
+      active = true;
+      (void)hipEventRecord(st->ev[st->recs.size() * 2], s);
+      st->recs.push_back({cls, flops, bytes});
+    }
+  }
+  ~Bracket() { if (active) (void)hipEventRecord(st->ev[(st->recs.size() - 1) * 2 + 1], s); }
+};
+
+// ---- typed operations ------------------------------------------------------
+
+template <typename T> struct GemmDispatch;
+
+template <> struct GemmDispatch<float> {
+  static hipError_t run(int op, int mode, int variant, int64_t M, int64_t N, int64_t K, const float* a,
+                        const float* b, const EpiArgs<float>& e, hipStream_t s) {
+    (void)variant;
+    if (op == GEMM_FWD) return launch_gemm_simple<float>(mode, a, K, 1, b, K, 1, M, N, K, e, s);
+    if (op == GEMM_DGRAD) return launch_gemm_simple<float>(mode, a, K, 1, b, 1, N, M, N, K, e, s);
+    return launch_gemm_simple<float>(mode, a, 1, M, b, 1, N, M, N, K, e, s);
+  }
+};
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+template <> struct GemmDispatch<bf16> {
+  // variant 0: library's choice; -1: force the simple kernel; >0: that MFMA configuration
+  static hipError_t run(int op, int mode, int variant, int64_t M, int64_t N, int64_t K, const bf16* a,
+                        const bf16* b, const EpiArgs<bf16>& e, hipStream_t s) {
+    const int64_t lda = (op == GEMM_WGRAD) ? M : K;
+    const int64_t ldb = (op == GEMM_FWD) ? K : N;
+    const bool ptr_ok = aligned16(a) && aligned16(b) && aligned16(e.bias) && aligned16(e.aux_in) &&
+                        aligned16(e.out) && aligned16(e.aux_out) && aligned16(e.out_f32) && (N % 8 == 0);
+    int v = variant;
+    if (v == 0) v = ptr_ok ? mg_choose_variant(M, N, K, lda, ldb) : -1;
+    if (v > 0) {
+      if (!ptr_ok || !mg_shape_ok(v, M, N, K, lda, ldb)) return hipErrorInvalidConfiguration;
+      return launch_gemm_mfma(op, mode, v, a, lda, b, ldb, M, N, K, e, s);
+    }
+    if (op == GEMM_FWD) return launch_gemm_simple<bf16>(mode, a, K, 1, b, K, 1, M, N, K, e, s);
+    if (op == GEMM_DGRAD) return launch_gemm_simple<bf16>(mode, a, K, 1, b, 1, N, M, N, K, e, s);
+    return launch_gemm_simple<bf16>(mode, a, 1, M, b, 1, N, M, N, K, e, s);
+  }
+};
+
+template <typename T> struct AttnDispatch {
+  static hipError_t fwd(int variant, const T* qkv, T* ctx, float* lse, int b, int s, int a, int d, int causal, hipStream_t st) {
+    (void)variant;
+    return launch_attention_fwd_simple<T>(qkv, ctx, lse, b, s, a, d, causal, st);
+  }
+  static hipError_t bwd(int variant, const T* qkv, const T* ctx, const float* lse, const T* dctx, T* dqkv,
+                        float* delta, int b, int s, int a, int d, int causal, hipStream_t st) {
+    (void)variant;
+    return launch_attention_bwd_simple<T>(qkv, ctx, lse, dctx, dqkv, delta, b, s, a, d, causal, st);
+  }
+};
+
+template <> struct AttnDispatch<bf16> {
+  // variant 0: library's choice; -1: simple kernels; 1: MFMA kernels
+  static hipError_t fwd(int variant, const bf16* qkv, bf16* ctx, float* lse, int b, int s, int a, int d, int causal, hipStream_t st) {
+    int v = variant;
+    if (v == 0) v = attn_mfma_supported(s, d) ? 1 : -1;
+    if (v == 1) {
+      if (!attn_mfma_supported(s, d)) return hipErrorInvalidConfiguration;
+      return launch_attention_fwd_mfma(qkv, ctx, lse, b, s, a, d, causal, st);
+    }
+    return launch_attention_fwd_simple<bf16>(qkv, ctx, lse, b, s, a, d, causal, st);
+  }
+  static hipError_t bwd(int variant, const bf16* qkv, const bf16* ctx, const float* lse, const bf16* dctx, bf16* dqkv,
+                        float* delta, int b, int s, int a, int d, int causal, hipStream_t st) {
+    int v = variant;
+    if (v == 0) v = attn_mfma_supported(s, d) ? 1 : -1;
+    if (v == 1) {
+      if (!attn_mfma_supported(s, d)) return hipErrorInvalidConfiguration;
+      return launch_attention_bwd_mfma(qkv, ctx, lse, dctx, dqkv, delta, b, s, a, d, causal, st);
+    }
+    return launch_attention_bwd_simple<bf16>(qkv, ctx, lse, dctx, dqkv, delta, b, s, a, d, causal, st);
+  }
+};
+
+// ---- the stage passes -------------------------------------------------------
+
+template <typename T>
+struct StageOps {
+  varuna_stage* S;
+  hipStream_t st;
+  const Dims& D;
+  StageOps(varuna_stage* s_, hipStream_t st_) : S(s_), st(st_), D(s_->D) {}
+
+  const T* param(int l, int which) const {
+    return reinterpret_cast<const T*>(S->params) + (size_t)l * S->po.per_layer + S->po.off[which];
+  }
+  float* grad(int l, int which) const { return S->grads + (size_t)l * S->po.per_layer + S->po.off[which]; }
+  template <typename U> U* wsp(size_t off) const { return reinterpret_cast<U*>(S->work + off); }
+
+  hipError_t gemm(int cls, int op, int mode, int64_t M, int64_t N, int64_t K, const T* a, const T* b, const T* bias,
+                  const T* aux_in, T* out, T* aux_out, float* out_f32) {
+    EpiArgs<T> e{bias, aux_in, out, aux_out, out_f32, N};
+    double bytes = (double)(M * K + N * K) * sizeof(T) + (double)M * N * (out_f32 ? 8.0 : (double)sizeof(T));
+    Bracket br(S, st, cls, 2.0 * M * N * K, bytes);
+    return GemmDispatch<T>::run(op, mode, 0, M, N, K, a, b, e, st);
+  }
+
+  double attn_flops_fwd() const {
+    double dense = 4.0 * D.b * D.a * (double)D.s * D.s * D.d;
+    return D.causal ? dense * 0.5 : dense;
+  }
+
+  // One layer forward.  save: also store stats, lse, u.  skip_mlp2: stop after GeLU.
+  hipError_t layer_forward(int l, const T* x, T* y, const LayerArea& A, bool save, bool skip_mlp2) {
+    hipError_t e;
+    const int64_t T_ = D.T;
+    T* xn1 = wsp<T>(A.xn1); T* qkv = wsp<T>(A.qkv); T* ctx = wsp<T>(A.ctx); T* x1 = wsp<T>(A.x1);
+    T* xn2 = wsp<T>(A.xn2); T* u = wsp<T>(A.u); T* g = wsp<T>(A.g);
+    float* stats1 = save ? wsp<float>(A.stats1) : nullptr;
+    float* stats2 = save ? wsp<float>(A.stats2) : nullptr;
+    float* lse = save ? wsp<float>(A.lse) : nullptr;
+    {
+      Bracket br(S, st, VARUNA_K_LN_FWD, 0, 2.0 * D.E * sizeof(T));
+      if ((e = launch_layernorm_fwd<T>(x, param(l, VARUNA_P_LN1_G), param(l, VARUNA_P_LN1_B), xn1, stats1, T_, D.h, D.eps, st))) return e;
+    }
+    if ((e = gemm(VARUNA_K_GEMM_FWD, GEMM_FWD, EPI_BIAS, T_, 3 * D.h, D.h, xn1, param(l, VARUNA_P_WQKV), param(l, VARUNA_P_BQKV), nullptr, qkv, nullptr, nullptr))) return e;
+    {
+      Bracket br(S, st, VARUNA_K_ATTN_FWD, attn_flops_fwd(), 4.0 * D.E * sizeof(T));
+      if ((e = AttnDispatch<T>::fwd(0, qkv, ctx, lse, D.b, D.s, D.a, D.d, D.causal, st))) return e;
+    }
+    if ((e = gemm(VARUNA_K_GEMM_FWD, GEMM_FWD, EPI_BIAS_RES, T_, D.h, D.h, ctx, param(l, VARUNA_P_WO), param(l, VARUNA_P_BO), x, x1, nullptr, nullptr))) return e;
+    {
+      Bracket br(S, st, VARUNA_K_LN_FWD, 0, 2.0 * D.E * sizeof(T));
+      if ((e = launch_layernorm_fwd<T>(x1, param(l, VARUNA_P_LN2_G), param(l, VARUNA_P_LN2_B), xn2, stats2, T_, D.h, D.eps, st))) return e;
+    }
+    if ((e = gemm(VARUNA_K_GEMM_FWD, GEMM_FWD, EPI_BIAS_GELU, T_, D.f, D.h, xn2, param(l, VARUNA_P_W1), param(l, VARUNA_P_B1), nullptr, g, save ? u : nullptr, nullptr))) return e;
+    if (skip_mlp2) return hipSuccess;
+    return gemm(VARUNA_K_GEMM_FWD, GEMM_FWD, EPI_BIAS_RES, T_, D.h, D.f, g, param(l, VARUNA_P_W2), param(l, VARUNA_P_B2), x1, y, nullptr, nullptr);
+  }
+
+  hipError_t colsum(const T* a, float* out, int64_t n) {
+    Bracket br(S, st, VARUNA_K_COLREDUCE, 0, (double)D.T * n * sizeof(T));
+    return launch_colsum<T>(a, out, wsp<float>(S->ws.partial), D.T, n, st);
+  }
+
+  // One layer backward.  x: the layer's input, dy: gradient of its output, dx: gradient of its input.
+  hipError_t layer_backward(int l, const T* x, const T* dy, T* dx, const LayerArea& A) {
+    hipError_t e;
+    const int64_t T_ = D.T;
+    const Workspace& W = S->ws;
+    const T* xn1 = wsp<T>(A.xn1); const T* qkv = wsp<T>(A.qkv); const T* ctx = wsp<T>(A.ctx);
+    const T* x1 = wsp<T>(A.x1); const T* xn2 = wsp<T>(A.xn2); const T* u = wsp<T>(A.u); const T* g = wsp<T>(A.g);
+    const float* stats1 = wsp<float>(A.stats1); const float* stats2 = wsp<float>(A.stats2);
+    const float* lse = wsp<float>(A.lse);
+    T* du = wsp<T>(W.du); T* dxn = wsp<T>(W.dxn); T* dx1 = wsp<T>(W.dx1); T* dctx = wsp<T>(W.dctx);
+    T* dqkv = wsp<T>(W.dqkv); float* delta = wsp<float>(W.delta); float* partial = wsp<float>(W.partial);
+
+    // MLP2: du = (dy W2) * GeLU'(u); dW2 += dy^T g; db2 += colsum(dy)
+    if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_DGELU, T_, D.f, D.h, dy, param(l, VARUNA_P_W2), nullptr, u, du, nullptr, nullptr))) return e;
+    if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.h, D.f, T_, dy, g, nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_W2)))) return e;
+    if ((e = colsum(dy, grad(l, VARUNA_P_B2), D.h))) return e;
+    // MLP1: dxn2 = du W1; dW1 += du^T xn2; db1 += colsum(du)
+    if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_PLAIN, T_, D.h, D.f, du, param(l, VARUNA_P_W1), nullptr, nullptr, dxn, nullptr, nullptr))) return e;
+    if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.f, D.h, T_, du, xn2, nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_W1)))) return e;
+    if ((e = colsum(du, grad(l, VARUNA_P_B1), D.f))) return e;
+    // LN2: dx1 = dy + LN'(dxn2)
+    {
+      Bracket br(S, st, VARUNA_K_LN_BWD, 0, 6.0 * D.E * sizeof(T));
+      if ((e = launch_layernorm_bwd<T>(dxn, x1, stats2, param(l, VARUNA_P_LN2_G), dy, dx1, grad(l, VARUNA_P_LN2_G), grad(l, VARUNA_P_LN2_B), partial, T_, D.h, st))) return e;
+    }
+    // proj: dctx = dx1 Wo; dWo += dx1^T ctx; dbo += colsum(dx1)
+    if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_PLAIN, T_, D.h, D.h, dx1, param(l, VARUNA_P_WO), nullptr, nullptr, dctx, nullptr, nullptr))) return e;
+    if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.h, D.h, T_, dx1, ctx, nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_WO)))) return e;
+    if ((e = colsum(dx1, grad(l, VARUNA_P_BO), D.h))) return e;
+    // attention
+    {
+      Bracket br(S, st, VARUNA_K_ATTN_BWD, 2.5 * attn_flops_fwd(), 9.0 * D.E * sizeof(T));
+      if ((e = AttnDispatch<T>::bwd(0, qkv, ctx, lse, dctx, dqkv, delta, D.b, D.s, D.a, D.d, D.causal, st))) return e;
+    }
+    // QKV: dxn1 = dqkv Wqkv; dWqkv += dqkv^T xn1; dbqkv += colsum(dqkv)
+    if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_PLAIN, T_, D.h, 3 * D.h, dqkv, param(l, VARUNA_P_WQKV), nullptr, nullptr, dxn, nullptr, nullptr))) return e;
+    if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, 3 * D.h, D.h, T_, dqkv, xn1, nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_WQKV)))) return e;
+    if ((e = colsum(dqkv, grad(l, VARUNA_P_BQKV), 3 * D.h))) return e;
+    // LN1: dx = dx1 + LN'(dxn1)
+    {
+      Bracket br(S, st, VARUNA_K_LN_BWD, 0, 6.0 * D.E * sizeof(T));
+      if ((e = launch_layernorm_bwd<T>(dxn, x, stats1, param(l, VARUNA_P_LN1_G), dx1, dx, grad(l, VARUNA_P_LN1_G), grad(l, VARUNA_P_LN1_B), partial, T_, D.h, st))) return e;
+    }
+    return hipSuccess;
+  }
+
+  T* slot(int mb) const { return reinterpret_cast<T*>(S->boundary) + (size_t)mb * D.E; }
+
+  hipError_t store_boundary(int mb, const T* x_in) {
+    if (x_in == slot(mb)) return hipSuccess;
+    Bracket br(S, st, VARUNA_K_OTHER, 0, 2.0 * D.E * sizeof(T));
+    return hipMemcpyAsync(slot(mb), x_in, (size_t)D.E * sizeof(T), hipMemcpyDeviceToDevice, st);
+  }
+
+  // Forward that keeps nothing but the boundary slot: every layer reuses area 0.
+  hipError_t forward(int mb, const T* x_in, T* y_out) {
+    hipError_t e;
+    if ((e = store_boundary(mb, x_in))) return e;
+    const T* x = slot(mb);
+    for (int l = 0; l < D.L; ++l) {
+      T* y = (l == D.L - 1) ? y_out : wsp<T>(S->ws.ping[l & 1]);
+      if ((e = layer_forward(l, x, y, S->ws.layer[0], false, false))) return e;
+      x = y;
+    }
+    return hipSuccess;
+  }
+
+  // Recompute from the boundary slot into the per-layer areas.  with_output: also
+  // produce the stage output (the debug hook wants it; the backward pass does not).
+  hipError_t recompute(int mb, T* y_out) {
+    hipError_t e;
+    const T* x = slot(mb);
+    for (int l = 0; l < D.L; ++l) {
+      const bool last = (l == D.L - 1);
+      T* y = last ? y_out : wsp<T>(S->ws.layer[l].y);
+      if ((e = layer_forward(l, x, y, S->ws.layer[l], true, last && y_out == nullptr))) return e;
+      x = y;
+    }
+    return hipSuccess;
+  }
+
+  hipError_t backward(int mb, const T* dy_in, T* dx_out) {
+    hipError_t e;
+    if ((e = recompute(mb, nullptr))) return e;
+    const T* dy = dy_in;
+    for (int l = D.L - 1; l >= 0; --l) {
+      const T* x = (l == 0) ? slot(mb) : wsp<T>(S->ws.layer[l - 1].y);
+      T* dx = (l == 0) ? dx_out : wsp<T>(S->ws.dping[l & 1]);
+      if ((e = layer_backward(l, x, dy, dx, S->ws.layer[l]))) return e;
+      dy = dx;
+    }
+    return hipSuccess;
+  }
+};
+
+varuna_status_t check_call(varuna_stage_t* st, int32_t mb, const void* in, void* out) {
+  if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
+  if (mb < 0 || mb >= st->D.M) return fail(VARUNA_EINVAL, "micro-batch slot %d out of range [0, %d)", mb, st->D.M);
+  if (!in || !out) return fail(VARUNA_EINVAL, "NULL tensor pointer");
+  return VARUNA_OK;
+}
+
+varuna_status_t hip_result(hipError_t e, const char* what) {
+  if (e == hipSuccess) return VARUNA_OK;
+  if (e == hipErrorInvalidConfiguration) return fail(VARUNA_EUNSUPPORTED, "%s: kernel configuration does not support this shape", what);
+  return fail(VARUNA_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+// ============================================================================
+// C ABI
+// ============================================================================
+extern "C" {
+
+const char* varuna_last_error(void) { return g_err; }
+
+varuna_status_t varuna_stage_query_sizes(const varuna_stage_config_t* cfg, size_t* param_bytes, size_t* grad_bytes,
+                                         size_t* boundary_bytes, size_t* workspace_bytes) {
+  Dims D;
+  varuna_status_t rc = make_dims(cfg, &D);
+  if (rc) return rc;
+  ParamOffsets po = param_offsets(D);
+  if (param_bytes) *param_bytes = po.per_layer * D.L * D.es;
+  if (grad_bytes) *grad_bytes = po.per_layer * D.L * sizeof(float);
+  if (boundary_bytes) *boundary_bytes = (size_t)D.M * D.E * D.es;
+  if (workspace_bytes) *workspace_bytes = carve(D).total;
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_stage_param_offset(const varuna_stage_config_t* cfg, int32_t layer, int32_t which,
+                                          size_t* offset_elems, size_t* n_elems) {
+  Dims D;
+  varuna_status_t rc = make_dims(cfg, &D);
+  if (rc) return rc;
+  if (layer < 0 || layer >= D.L) return fail(VARUNA_EINVAL, "layer %d out of range [0, %d)", layer, D.L);
+  if (which < 0 || which >= VARUNA_PARAMS_PER_LAYER) return fail(VARUNA_EINVAL, "parameter index %d out of range", which);
+  ParamOffsets po = param_offsets(D);
+  if (offset_elems) *offset_elems = (size_t)layer * po.per_layer + po.off[which];
+  if (n_elems) *n_elems = po.n[which];
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_stage_create(const varuna_stage_config_t* cfg, const void* params, void* grads_f32,
+                                    void* boundary, void* workspace, varuna_stage_t** out) {
+  if (!out) return fail(VARUNA_EINVAL, "out handle pointer is NULL");
+  *out = nullptr;
+  Dims D;
+  varuna_status_t rc = make_dims(cfg, &D);
+  if (rc) return rc;
+  if (!params || !grads_f32 || !boundary || !workspace) return fail(VARUNA_EINVAL, "NULL device buffer");
+  const void* ptrs[4] = {params, grads_f32, boundary, workspace};
+  for (const void* p : ptrs)
+    if (reinterpret_cast<uintptr_t>(p) % 256 != 0) return fail(VARUNA_EINVAL, "device buffers must be 256-byte aligned");
+  varuna_stage* st = new (std::nothrow) varuna_stage();
+  if (!st) return fail(VARUNA_ENOMEM, "out of host memory");
+  st->D = D;
+  st->po = param_offsets(D);
+  st->ws = carve(D);
+  st->params = static_cast<const char*>(params);
+  st->grads = static_cast<float*>(grads_f32);
+  st->boundary = static_cast<char*>(boundary);
+  st->work = static_cast<char*>(workspace);
+  st->forwarded.assign(D.M, 0);
+  *out = st;
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_stage_destroy(varuna_stage_t* st) {
+  if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
+  for (hipEvent_t e : st->ev) (void)hipEventDestroy(e);
+  delete st;
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_stage_forward(varuna_stage_t* st, int32_t mb, const void* x_in, void* y_out, void* hip_stream) {
+  varuna_status_t rc = check_call(st, mb, x_in, y_out);
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = (st->D.dtype == VARUNA_F32)
+                     ? StageOps<float>(st, s).forward(mb, static_cast<const float*>(x_in), static_cast<float*>(y_out))
+                     : StageOps<bf16>(st, s).forward(mb, static_cast<const bf16*>(x_in), static_cast<bf16*>(y_out));
+  if ((rc = hip_result(e, "varuna_stage_forward"))) return rc;
+  st->forwarded[mb] = 1;
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_stage_debug_forward_save(varuna_stage_t* st, int32_t mb, const void* x_in, void* y_out, void* hip_stream) {
+  varuna_status_t rc = check_call(st, mb, x_in, y_out);
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (st->D.dtype == VARUNA_F32) {
+    StageOps<float> ops(st, s);
+    e = ops.store_boundary(mb, static_cast<const float*>(x_in));
+    if (e == hipSuccess) e = ops.recompute(mb, static_cast<float*>(y_out));
+  } else {
+    StageOps<bf16> ops(st, s);
+    e = ops.store_boundary(mb, static_cast<const bf16*>(x_in));
+    if (e == hipSuccess) e = ops.recompute(mb, static_cast<bf16*>(y_out));
+  }
+  if ((rc = hip_result(e, "varuna_stage_debug_forward_save"))) return rc;
+  st->forwarded[mb] = 1;
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_stage_debug_saved_region(const varuna_stage_t* st, size_t* offset_bytes, size_t* n_bytes) {
+  if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
+  if (offset_bytes) *offset_bytes = st->ws.saved_begin;
+  if (n_bytes) *n_bytes = st->ws.saved_end - st->ws.saved_begin;
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_stage_backward_recompute(varuna_stage_t* st, int32_t mb, const void* dy_in, void* dx_out, void* hip_stream) {
+  varuna_status_t rc = check_call(st, mb, dy_in, dx_out);
+  if (rc) return rc;
+  if (!st->forwarded[mb]) return fail(VARUNA_ESTATE, "backward_recompute(%d) without a forward of that slot", mb);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = (st->D.dtype == VARUNA_F32)
+                     ? StageOps<float>(st, s).backward(mb, static_cast<const float*>(dy_in), static_cast<float*>(dx_out))
+                     : StageOps<bf16>(st, s).backward(mb, static_cast<const bf16*>(dy_in), static_cast<bf16*>(dx_out));
+  if ((rc = hip_result(e, "varuna_stage_backward_recompute"))) return rc;
+  st->forwarded[mb] = 0;
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_stage_grad_accum_reset(varuna_stage_t* st, void* hip_stream) {
+  if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const size_t n = st->po.per_layer * st->D.L;
+  Bracket br(st, s, VARUNA_K_OTHER, 0, 4.0 * n);
+  hipLaunchKernelGGL(fill_zero_f32_kernel, dim3(2048), dim3(256), 0, s, st->grads, n);
+  return hip_result(hipGetLastError(), "varuna_stage_grad_accum_reset");
+}
+
+varuna_status_t varuna_stage_profile_enable(varuna_stage_t* st, int32_t on) {
+  if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
+  if (on && st->ev.empty()) {
+    st->ev.reserve(2 * kMaxEvents);
+    for (int i = 0; i < 2 * kMaxEvents; ++i) {
+      hipEvent_t e;
+      HIP_TRY(hipEventCreate(&e));
+      st->ev.push_back(e);
+    }
+  }
+  st->prof_on = on != 0;
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_stage_profile_collect(varuna_stage_t* st, double* ms, int64_t* launches, double* flops, double* bytes) {
+  if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
+  for (int i = 0; i < VARUNA_K_COUNT; ++i) {
+    if (ms) ms[i] = 0;
+    if (launches) launches[i] = 0;
+    if (flops) flops[i] = 0;
+    if (bytes) bytes[i] = 0;
+  }
+  for (size_t i = 0; i < st->recs.size(); ++i) {
+    HIP_TRY(hipEventSynchronize(st->ev[2 * i + 1]));
+    float t = 0.f;
+    HIP_TRY(hipEventElapsedTime(&t, st->ev[2 * i], st->ev[2 * i + 1]));
+    const int c = st->recs[i].cls;
+    if (ms) ms[c] += t;
+    if (launches) launches[c] += 1;
+    if (flops) flops[c] += st->recs[i].flops;
+    if (bytes) bytes[c] += st->recs[i].bytes;
+  }
+  st->recs.clear();
+  return VARUNA_OK;
+}
+
+// ---- single operations -------------------------------------------------------
+
+varuna_status_t varuna_op_gemm(int32_t dtype, int32_t op, int32_t epi, int32_t variant, int64_t M, int64_t N, int64_t K,
+                               const void* a, const void* b, const void* bias, const void* aux_in, void* out,
+                               void* aux_out, void* hip_stream) {
+  if (M < 1 || N < 1 || K < 1 || M > (1ll << 30) || N > (1ll << 30) || K > (1ll << 30)) return fail(VARUNA_EINVAL, "bad GEMM size");
+  if (!a || !b || !out) return fail(VARUNA_EINVAL, "NULL operand");
+  int mode;
+  if (op == GEMM_FWD && epi >= 0 && epi <= 2) mode = epi;
+  else if (op == GEMM_DGRAD && (epi == 0 || epi == 3)) mode = epi == 0 ? EPI_PLAIN : EPI_DGELU;
+  else if (op == GEMM_WGRAD && epi == 0) mode = EPI_ACCUM_F32;
+  else return fail(VARUNA_EINVAL, "unknown op/epilogue combination %d/%d", op, epi);
+  if (op == GEMM_FWD && !bias) return fail(VARUNA_EINVAL, "forward GEMM needs a bias");
+  if ((mode == EPI_BIAS_RES || mode == EPI_DGELU) && !aux_in) return fail(VARUNA_EINVAL, "epilogue needs aux_in");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (dtype == VARUNA_F32) {
+    EpiArgs<float> ea{static_cast<const float*>(bias), static_cast<const float*>(aux_in), static_cast<float*>(out),
+                      static_cast<float*>(aux_out), static_cast<float*>(out), N};
+    e = GemmDispatch<float>::run(op, mode, variant, M, N, K, static_cast<const float*>(a), static_cast<const float*>(b), ea, s);
+  } else if (dtype == VARUNA_BF16) {
+    EpiArgs<bf16> ea{static_cast<const bf16*>(bias), static_cast<const bf16*>(aux_in), static_cast<bf16*>(out),
+                     static_cast<bf16*>(aux_out), static_cast<float*>(out), N};
+    e = GemmDispatch<bf16>::run(op, mode, variant, M, N, K, static_cast<const bf16*>(a), static_cast<const bf16*>(b), ea, s);
+  } else {
+    return fail(VARUNA_EINVAL, "unknown dtype %d", dtype);
+  }
+  return hip_result(e, "varuna_op_gemm");
+}
+
+varuna_status_t varuna_op_layernorm_fwd(int32_t dtype, int64_t rows, int64_t h, float eps, const void* x, const void* gamma,
+                                        const void* beta, void* y, float* stats_f32, void* hip_stream) {
+  if (rows < 1 || h < 1 || h > (1 << 20) || !x || !gamma || !beta || !y) return fail(VARUNA_EINVAL, "bad layernorm arguments");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (dtype == VARUNA_F32)
+    e = launch_layernorm_fwd<float>(static_cast<const float*>(x), static_cast<const float*>(gamma), static_cast<const float*>(beta), static_cast<float*>(y), stats_f32, rows, (int)h, eps, s);
+  else if (dtype == VARUNA_BF16)
+    e = launch_layernorm_fwd<bf16>(static_cast<const bf16*>(x), static_cast<const bf16*>(gamma), static_cast<const bf16*>(beta), static_cast<bf16*>(y), stats_f32, rows, (int)h, eps, s);
+  else return fail(VARUNA_EINVAL, "unknown dtype %d", dtype);
+  return hip_result(e, "varuna_op_layernorm_fwd");
+}
+
+varuna_status_t varuna_op_layernorm_bwd(int32_t dtype, int64_t rows, int64_t h, const void* dy, const void* x,
+                                        const float* stats_f32, const void* gamma, const void* res, void* dx,
+                                        float* dgamma_f32, float* dbeta_f32, float* partial_f32, void* hip_stream) {
+  if (rows < 1 || h < 1 || h > (1 << 20) || !dy || !x || !stats_f32 || !gamma || !res || !dx || !dgamma_f32 || !dbeta_f32 || !partial_f32)
+    return fail(VARUNA_EINVAL, "bad layernorm backward arguments");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (dtype == VARUNA_F32)
+    e = launch_layernorm_bwd<float>(static_cast<const float*>(dy), static_cast<const float*>(x), stats_f32, static_cast<const float*>(gamma), static_cast<const float*>(res), static_cast<float*>(dx), dgamma_f32, dbeta_f32, partial_f32, rows, (int)h, s);
+  else if (dtype == VARUNA_BF16)
+    e = launch_layernorm_bwd<bf16>(static_cast<const bf16*>(dy), static_cast<const bf16*>(x), stats_f32, static_cast<const bf16*>(gamma), static_cast<const bf16*>(res), static_cast<bf16*>(dx), dgamma_f32, dbeta_f32, partial_f32, rows, (int)h, s);
+  else return fail(VARUNA_EINVAL, "unknown dtype %d", dtype);
+  return hip_result(e, "varuna_op_layernorm_bwd");
+}
+
+size_t varuna_op_colreduce_scratch_bytes(int64_t rows, int64_t n) {
+  if (rows < 1 || n < 1) return 0;
+  return (size_t)colreduce_chunks(rows) * (size_t)n * sizeof(float);
+}
+
+varuna_status_t varuna_op_colsum(int32_t dtype, int64_t rows, int64_t n, const void* a, float* out_f32, float* partial_f32, void* hip_stream) {
+  if (rows < 1 || n < 1 || !a || !out_f32 || !partial_f32) return fail(VARUNA_EINVAL, "bad colsum arguments");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (dtype == VARUNA_F32) e = launch_colsum<float>(static_cast<const float*>(a), out_f32, partial_f32, rows, n, s);
+  else if (dtype == VARUNA_BF16) e = launch_colsum<bf16>(static_cast<const bf16*>(a), out_f32, partial_f32, rows, n, s);
+  else return fail(VARUNA_EINVAL, "unknown dtype %d", dtype);
+  return hip_result(e, "varuna_op_colsum");
+}
+
+static varuna_status_t check_attn(int32_t b, int32_t s, int32_t heads, int32_t d) {
+  if (b < 1 || s < 1 || heads < 1 || d < 1) return fail(VARUNA_EINVAL, "non-positive attention dimension");
+  if (s > ATS_MAX_S || d > ATS_MAX_D) return fail(VARUNA_EUNSUPPORTED, "attention shape exceeds supported maximum");
+  if (b > 65535 || heads > 65535) return fail(VARUNA_EUNSUPPORTED, "too many batch elements or heads");
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_op_attention_fwd(int32_t dtype, int32_t variant, int32_t b, int32_t s, int32_t heads, int32_t d,
+                                        int32_t causal, const void* qkv, void* ctx, float* lse_f32, void* hip_stream) {
+  varuna_status_t rc = check_attn(b, s, heads, d);
+  if (rc) return rc;
+  if (!qkv || !ctx) return fail(VARUNA_EINVAL, "NULL tensor pointer");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (dtype == VARUNA_F32) e = AttnDispatch<float>::fwd(variant, static_cast<const float*>(qkv), static_cast<float*>(ctx), lse_f32, b, s, heads, d, causal, st);
+  else if (dtype == VARUNA_BF16) e = AttnDispatch<bf16>::fwd(variant, static_cast<const bf16*>(qkv), static_cast<bf16*>(ctx), lse_f32, b, s, heads, d, causal, st);
+  else return fail(VARUNA_EINVAL, "unknown dtype %d", dtype);
+  return hip_result(e, "varuna_op_attention_fwd");
+}
+
+varuna_status_t varuna_op_attention_bwd(int32_t dtype, int32_t variant, int32_t b, int32_t s, int32_t heads, int32_t d,
+                                        int32_t causal, const void* qkv, const void* ctx, const float* lse_f32,
+                                        const void* dctx, void* dqkv, float* delta_f32, void* hip_stream) {
+  varuna_status_t rc = check_attn(b, s, heads, d);
+  if (rc) return rc;
+  if (!qkv || !ctx || !lse_f32 || !dctx || !dqkv || !delta_f32) return fail(VARUNA_EINVAL, "NULL tensor pointer");
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (dtype == VARUNA_F32) e = AttnDispatch<float>::bwd(variant, static_cast<const float*>(qkv), static_cast<const float*>(ctx), lse_f32, static_cast<const float*>(dctx), static_cast<float*>(dqkv), delta_f32, b, s, heads, d, causal, st);
+  else if (dtype == VARUNA_BF16) e = AttnDispatch<bf16>::bwd(variant, static_cast<const bf16*>(qkv), static_cast<const bf16*>(ctx), lse_f32, static_cast<const bf16*>(dctx), static_cast<bf16*>(dqkv), delta_f32, b, s, heads, d, causal, st);
+  else return fail(VARUNA_EINVAL, "unknown dtype %d", dtype);
+  return hip_result(e, "varuna_op_attention_bwd");
+}
+
+}  // extern "C"

@@ -1,0 +1,166 @@
+"""GPU parity of the individual kernels (GEMM variants and epilogues, LayerNorm,
+column reductions, attention) against the fp64 oracle's pieces."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import stage_oracle as O
+from paper_2111_04007_amd import binding as B
+from paper_2111_04007_amd.synth import to_f64
+
+pytestmark = pytest.mark.gpu
+
+DT = {"f32": torch.float32, "bf16": torch.bfloat16}
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def rnd(shape, dtype, seed, scale=1.0):
+    g = np.random.Generator(np.random.Philox(key=[seed, 99]))
+    return torch.from_numpy(g.standard_normal(shape) * scale).to(DT[dtype]).cuda()
+
+
+def run_gemm_case(dtype, M, N, K, variant, seed=1):
+    """All six op/epilogue combinations for one shape and kernel configuration."""
+    x = rnd((M, K), dtype, seed)                # forward input / dgrad dY has shape [M,K]
+    w = rnd((N, K), dtype, seed + 1, 0.05)      # forward weight [N,K]
+    bias = rnd((N,), dtype, seed + 2, 0.5)
+    res = rnd((M, N), dtype, seed + 3)
+    x64, w64, b64, r64 = map(to_f64, (x, w, bias, res))
+    tol = TOL[dtype]
+    out = torch.empty((M, N), dtype=DT[dtype], device="cuda")
+    aux = torch.empty_like(out)
+    # forward, bias
+    B.op_gemm(B.OP_FWD, 0, x, w, out, bias=bias, variant=variant, M=M, N=N, K=K)
+    assert O.rel_l2(to_f64(out), O.linear_forward(x64, w64, b64)) <= tol
+    # forward, bias + GeLU, also storing u
+    B.op_gemm(B.OP_FWD, 1, x, w, out, bias=bias, aux_out=aux, variant=variant, M=M, N=N, K=K)
+    u64 = O.linear_forward(x64, w64, b64)
+    assert O.rel_l2(to_f64(aux), u64) <= tol
+    assert O.rel_l2(to_f64(out), O.gelu_tanh(u64)) <= tol
+    # forward, bias + residual
+    B.op_gemm(B.OP_FWD, 2, x, w, out, bias=bias, aux_in=res, variant=variant, M=M, N=N, K=K)
+    assert O.rel_l2(to_f64(out), r64 + O.linear_forward(x64, w64, b64)) <= tol
+    # dgrad: dX[M,N] = dY[M,K] W[K,N]
+    wd = rnd((K, N), dtype, seed + 4, 0.05)
+    B.op_gemm(B.OP_DGRAD, 0, x, wd, out, variant=variant, M=M, N=N, K=K)
+    ref = x64 @ to_f64(wd)
+    assert O.rel_l2(to_f64(out), ref) <= tol
+    B.op_gemm(B.OP_DGRAD, 3, x, wd, out, aux_in=res, variant=variant, M=M, N=N, K=K)
+    assert O.rel_l2(to_f64(out), ref * O.gelu_tanh_grad(r64)) <= tol
+    # wgrad: dW[M,N] += dY[K,M]^T X[K,N], twice to see the accumulation
+    dy = rnd((K, M), dtype, seed + 5)
+    xx = rnd((K, N), dtype, seed + 6)
+    acc = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        B.op_gemm(B.OP_WGRAD, 0, dy, xx, acc, variant=variant, M=M, N=N, K=K)
+    _, dw, _ = O.linear_backward(to_f64(dy), to_f64(xx), np.zeros((M, N)))
+    assert O.rel_l2(to_f64(acc), 0.5 + 2 * dw) <= tol
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("shape", [(128, 384, 128), (70, 45, 33), (1, 1, 1), (65, 64, 17)])
+def test_gemm_fp32(shape):
+    run_gemm_case("f32", *shape, variant=0)
+
+
+@pytest.mark.parametrize("shape", [(96, 200, 72), (64, 8, 40)])
+def test_gemm_bf16_simple_kernel(shape):
+    run_gemm_case("bf16", *shape, variant=-1)
+
+
+@pytest.mark.parametrize("variant,shape", [
+    (1, (512, 768, 256)), (2, (512, 768, 256)), (3, (512, 384, 192)), (4, (384, 640, 320)),
+    (2, (256, 256, 64)), (4, (128, 128, 64)),
+])
+def test_gemm_bf16_mfma_variants(variant, shape):
+    """Each MFMA tile configuration on several tiles, k-steps and a single-k-step case."""
+    run_gemm_case("bf16", *shape, variant=variant, seed=variant)
+
+
+def test_gemm_bf16_auto_choice_and_unsupported_variant():
+    run_gemm_case("bf16", 512, 1024, 512, variant=0)
+    a = rnd((100, 64), "bf16", 1)
+    w = rnd((128, 64), "bf16", 2)
+    out = torch.empty((100, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.VarunaError) as ei:
+        B.op_gemm(B.OP_FWD, 0, a, w, out, bias=w[0].contiguous(), variant=4, M=100, N=128, K=64)
+    assert ei.value.code == B.EUNSUPPORTED
+
+
+@pytest.mark.parametrize("dtype,rows,h", [("f32", 130, 128), ("f32", 5, 37), ("bf16", 257, 1024), ("bf16", 9, 100)])
+def test_layernorm_fwd_bwd(dtype, rows, h):
+    x = rnd((rows, h), dtype, 3, 2.0) + 0.5
+    gamma = (rnd((h,), dtype, 4, 0.2) + 1.0).to(DT[dtype])
+    beta = rnd((h,), dtype, 5, 0.2)
+    y = torch.empty_like(x)
+    stats = torch.empty(2 * rows, dtype=torch.float32, device="cuda")
+    B.op_layernorm_fwd(x, gamma, beta, y, stats)
+    y64, xhat, rstd = O.layernorm_forward(to_f64(x), to_f64(gamma), to_f64(beta), 1e-5)
+    tol = TOL[dtype]
+    assert O.rel_l2(to_f64(y), y64) <= tol
+    assert O.rel_l2(to_f64(stats[:rows]), to_f64(x).mean(axis=1)) <= 1e-5
+    assert O.rel_l2(to_f64(stats[rows:]), rstd[:, 0]) <= 1e-5
+    dy = rnd((rows, h), dtype, 6)
+    res = rnd((rows, h), dtype, 7)
+    dx = torch.empty_like(x)
+    dg = torch.full((h,), 0.25, dtype=torch.float32, device="cuda")
+    db = torch.full((h,), -0.25, dtype=torch.float32, device="cuda")
+    partial = torch.empty(B.colreduce_scratch_bytes(rows, 2 * h) // 4, dtype=torch.float32, device="cuda")
+    B.op_layernorm_bwd(dy, x, stats, gamma, res, dx, dg, db, partial)
+    dx64, dg64, db64 = O.layernorm_backward(to_f64(dy), xhat, rstd, to_f64(gamma))
+    assert O.rel_l2(to_f64(dx), to_f64(res) + dx64) <= tol
+    assert O.rel_l2(to_f64(dg), 0.25 + dg64) <= max(tol, 1e-5) * (1 if dtype == "f32" else 0.1)
+    assert O.rel_l2(to_f64(db), -0.25 + db64) <= max(tol, 1e-5) * (1 if dtype == "f32" else 0.1)
+
+
+@pytest.mark.parametrize("dtype,rows,n", [("f32", 300, 70), ("bf16", 1025, 384), ("bf16", 3, 8)])
+def test_colsum(dtype, rows, n):
+    a = rnd((rows, n), dtype, 8)
+    out = torch.full((n,), 1.0, dtype=torch.float32, device="cuda")
+    partial = torch.empty(B.colreduce_scratch_bytes(rows, n) // 4, dtype=torch.float32, device="cuda")
+    B.op_colsum(a, out, partial)
+    assert O.rel_l2(to_f64(out), 1.0 + to_f64(a).sum(axis=0)) <= 1e-5
+
+
+def run_attention_case(dtype, b, s, heads, d, causal, variant, seed=20):
+    h = heads * d
+    sh = O.StageShape(1, h, heads, s, b, 4 * h, bool(causal))
+    qkv = rnd((b * s, 3 * h), dtype, seed, 1.0)
+    dctx = rnd((b * s, h), dtype, seed + 1)
+    ctx = torch.empty((b * s, h), dtype=DT[dtype], device="cuda")
+    lse = torch.empty(b * heads * s, dtype=torch.float32, device="cuda")
+    B.op_attention_fwd(qkv, ctx, lse, b, s, heads, d, causal, variant=variant)
+    ctx64, probs = O.attention_forward(to_f64(qkv), sh)
+    tol = TOL[dtype]
+    assert O.rel_l2(to_f64(ctx), ctx64) <= tol
+    # log-sum-exp of the scaled, masked scores (natural log)
+    q64 = to_f64(qkv)
+    want = np.empty((b, heads, s))
+    for bi in range(b):
+        for j in range(heads):
+            q = q64[bi * s:(bi + 1) * s, j * d:(j + 1) * d]
+            k = q64[bi * s:(bi + 1) * s, h + j * d:h + (j + 1) * d]
+            sc = q @ k.T / np.sqrt(d)
+            if causal:
+                sc = np.where(np.triu(np.ones((s, s), bool), 1), -np.inf, sc)
+            mx = sc.max(axis=1)
+            want[bi, j] = mx + np.log(np.exp(sc - mx[:, None]).sum(axis=1))
+    assert np.abs(to_f64(lse).reshape(b, heads, s) - want).max() <= (1e-4 if dtype == "f32" else 2e-2)
+    dqkv = torch.empty_like(qkv)
+    delta = torch.empty_like(lse)
+    B.op_attention_bwd(qkv, ctx, lse, dctx, dqkv, delta, b, s, heads, d, causal, variant=variant)
+    ref = O.attention_backward(to_f64(dctx), q64, probs, sh)
+    got = to_f64(dqkv)
+    for part, name in ((slice(0, h), "dq"), (slice(h, 2 * h), "dk"), (slice(2 * h, 3 * h), "dv")):
+        assert O.rel_l2(got[:, part], ref[:, part]) <= tol, name
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("b,s,heads,d,causal", [(2, 64, 2, 64, 1), (3, 37, 3, 24, 0), (1, 1, 1, 8, 1), (1, 130, 2, 96, 1)])
+def test_attention_fp32(b, s, heads, d, causal):
+    run_attention_case("f32", b, s, heads, d, causal, variant=0)
+
+
+@pytest.mark.parametrize("b,s,heads,d,causal", [(2, 128, 2, 64, 1), (1, 200, 2, 96, 0), (1, 256, 1, 128, 1)])
+def test_attention_bf16_simple(b, s, heads, d, causal):
+    run_attention_case("bf16", b, s, heads, d, causal, variant=-1)

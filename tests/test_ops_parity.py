@@ -152,7 +152,10 @@ def run_attention_case(dtype, b, s, heads, d, causal, variant, seed=20):
     ref = O.attention_backward(to_f64(dctx), q64, probs, sh)
     got = to_f64(dqkv)
     for part, name in ((slice(0, h), "dq"), (slice(h, 2 * h), "dk"), (slice(2 * h, 3 * h), "dv")):
-        assert O.rel_l2(got[:, part], ref[:, part]) <= tol, name
+        if np.linalg.norm(ref[:, part]) > 0:
+            assert O.rel_l2(got[:, part], ref[:, part]) <= tol, name
+        else:   # s = 1: dQ and dK are exactly zero; measure against the scale of the whole gradient
+            assert np.linalg.norm(got[:, part]) <= tol * np.linalg.norm(ref), name
     torch.cuda.synchronize()
 
 

@@ -1,0 +1,324 @@
+// bf16 MFMA GEMM for gfx950, second generation: operands go from global memory
+// straight into LDS (global_load_lds_dwordx4, no register staging) into two
+// stages of 64 k, and MFMA fragments are software-pipelined in registers across
+// k-steps and across k-tiles, with one workgroup barrier per k-tile.
+//
+//   acc[m,n] = sum_k A(m,k) * B(n,k)
+//   A_KMAJOR: A(m,k) = a[m*lda + k]   else (m-major): A(m,k) = a[k*lda + m]
+//   B_KMAJOR: B(n,k) = b[n*ldb + k]   else (n-major): B(n,k) = b[k*ldb + n]
+//
+// LDS layouts (each wave-level direct load deposits 64 lanes x 16 B contiguously,
+// so swizzles are applied by choosing which global chunk a lane fetches):
+//   k-major operand : [row][64 k]  (128 B per row, 8 chunks of 16 B),
+//                     physical chunk = c ^ ((row ^ (row >> 3)) & 7); fragments by ds_read_b128.
+//   m/n-major operand: [k][ROWS]   (ROWS*2 B per k-row), physical chunk within each
+//                     group of 8 = c ^ ((k & 3) << 1); fragments by the transposing
+//                     LDS read ds_read_b64_tr_b16 (16 lanes x 4 k-rows -> each lane
+//                     gets 4 consecutive k of its own row), two per 8-k operand.
+// Both give a lane the 8 consecutive k-values (lane/32)*8.. of tile row lane%32,
+// which is the operand layout of v_mfma_f32_32x32x16_bf16.
+#pragma once
+#include <cstdlib>
+#include <type_traits>
+
+#include "common.h"
+#include "gemm_mfma.h"  // mg_epilogue4, GemmOp
+
+namespace varuna {
+
+constexpr int DG_BK = 64;      // k per LDS stage: 128-byte row segments keep the L1/L2 path efficient
+constexpr int DG_STAGES = 2;
+
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* glb_ptr_t;
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8]).
+#define DG_WAIT_VM(n) (((n) & 0xf) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+#define DG_WAIT_VM0_LGKM0 (7 << 4)
+
+// Direct global->LDS staging of one operand tile (ROWS x 64).
+//   k-major  : LDS [row][64 k], 8 chunks of 16 B per row, physical chunk = c ^ ((row ^ (row >> 3)) & 7)
+//   m/n-major: LDS [k][ROWS],   physical chunk (within each aligned group of 8) = c ^ ((k & 3) << 1)
+template <int ROWS, int NW, bool KMAJOR>
+struct DgLoader {
+  static constexpr int NINS = ROWS * DG_BK * 2 / 1024;  // wave-level 1 KB loads per tile
+  static constexpr int LPT = NINS / NW;                  // per wave
+  static_assert(NINS % NW == 0 && LPT >= 1, "tile rows / waves mismatch");
+  const bf16* gp[LPT];  // per-lane source of each of this wave's loads (k-tile 0)
+  int64_t step;         // elements to advance per k-tile
+
+  __device__ __forceinline__ void init(const bf16* g, int64_t ld, int64_t row0, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      const int q = wave + i * NW;
+      if (KMAJOR) {
+        const int row = q * 8 + (lane >> 3), p = lane & 7;
+        const int c = p ^ ((row ^ (row >> 3)) & 7);
+        gp[i] = g + (row0 + row) * ld + c * 8;
+      } else {
+        constexpr int CPR = ROWS / 8;  // chunks per k-row
+        const int slot = q * 64 + lane, krow = slot / CPR, p = slot % CPR;
+        const int c = p ^ ((krow & 3) << 1);
+        gp[i] = g + (int64_t)krow * ld + row0 + c * 8;
+      }
+    }
+    step = KMAJOR ? (int64_t)DG_BK : (int64_t)DG_BK * ld;
+  }
+
+  __device__ __forceinline__ void issue(bf16* lds_tile, int kt, int wave) const {
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      const int q = wave + i * NW;
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(gp[i] + kt * step), (lds_ptr_t)(lds_tile + q * 512), 16, 0, 0);
+    }
+  }
+};
+
+// Fragment reader: the 8 consecutive k-values ks*16 + (lane/32)*8 .. of tile row row_base + lane%32.
+template <int ROWS, bool KMAJOR>
+struct DgFrag {
+  static __device__ __forceinline__ bf16x8 read(const bf16* lds_tile, int row_base, int ks, int lane) {
+    if (KMAJOR) {
+      const int row = row_base + (lane & 31), c = ks * 2 + (lane >> 5);
+      return *reinterpret_cast<const bf16x8*>(lds_tile + row * DG_BK + ((c ^ ((row ^ (row >> 3)) & 7)) << 3));
+    } else {
+      const int blk = lane >> 4, j = lane & 15;
+      const int m = row_base + (blk & 1) * 16 + 4 * (j & 3);
+      const int kq = j >> 2;  // k-row within its group of 4 == (krow & 3)
+      const int c = m >> 3, phys = c ^ (kq << 1);
+      const bf16* p0 = lds_tile + (ks * 16 + (blk >> 1) * 8 + kq) * ROWS + phys * 8 + (m & 7);
+      shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)p0);
+      shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)(p0 + 4 * ROWS));
+      union { struct { shortx4 a, b; } s; bf16x8 v; } u;
+      u.s.a = lo; u.s.b = hi;
+      return u.v;
+    }
+  }
+};
+
+// Scheduling hints for one k-step: MFMA, then RPM LDS reads (and one direct load if any
+// are pending in this step), MFMA, ...
+template <int Q, int NMFMA, int NREAD, int RPM, int NVMEM>
+struct DgInterleave {
+  static __device__ __forceinline__ void hint() {
+    if constexpr (Q < NMFMA) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if constexpr (Q * RPM < NREAD)
+        __builtin_amdgcn_sched_group_barrier(0x100, (Q * RPM + RPM <= NREAD) ? RPM : NREAD - Q * RPM, 0);
+      if constexpr (Q < NVMEM) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      DgInterleave<Q + 1, NMFMA, NREAD, RPM, NVMEM>::hint();
+    }
+  }
+};
+
+template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, int MODE>
+__global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
+    const bf16* __restrict__ a, int64_t lda, const bf16* __restrict__ b, int64_t ldb, int K,
+    int tiles_m, int tiles_n, EpiArgs<bf16> epi, int xcd_remap, int group) {
+  constexpr int NW = WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int STAGE_ELEMS = (BM + BN) * DG_BK;
+  extern __shared__ __attribute__((aligned(16))) unsigned char dg_smem[];
+  bf16* smem = reinterpret_cast<bf16*>(dg_smem);  // [2][A tile | B tile]
+
+  const int tid = threadIdx.x, lane = tid % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  // Workgroup -> tile.  Consecutive workgroup ids go round-robin over the 8 XCDs; give
+  // every XCD a contiguous range of logical tiles, walked in groups of `group` tile rows
+  // so the A and B panels an XCD touches stay in its L2.
+  int logical = blockIdx.x;
+  const int nblk = gridDim.x;
+  if (xcd_remap && (nblk & 7) == 0) logical = (blockIdx.x & 7) * (nblk >> 3) + (blockIdx.x >> 3);
+  const int width = group * tiles_n;
+  const int grp = logical / width;
+  const int first_m = grp * group;
+  const int gsize = (tiles_m - first_m < group) ? tiles_m - first_m : group;
+  const int tile_m = first_m + (logical % width) % gsize;
+  const int tile_n = (logical % width) / gsize;
+  const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+
+  DgLoader<BM, NW, A_KMAJOR> la;
+  DgLoader<BN, NW, B_KMAJOR> lb;
+  la.init(a, lda, m0, wave, lane);
+  lb.init(b, ldb, n0, wave, lane);
+  constexpr int LPT = DgLoader<BM, NW, A_KMAJOR>::LPT + DgLoader<BN, NW, B_KMAJOR>::LPT;
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = K / DG_BK;
+  la.issue(smem, 0, wave);
+  lb.issue(smem + BM * DG_BK, 0, wave);
+  if (nk > 1) {
+    la.issue(smem + STAGE_ELEMS, 1, wave);
+    lb.issue(smem + STAGE_ELEMS + BM * DG_BK, 1, wave);
+    __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LPT));  // tile 0 landed, tile 1 may be in flight
+  } else {
+    __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(0));
+  }
+  __builtin_amdgcn_s_barrier();
+
+  bf16x8 fa[2][TM], fb[2][TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) fb[0][j] = DgFrag<BN, B_KMAJOR>::read(smem + BM * DG_BK, wn * WN + j * 32, 0, lane);
+#pragma unroll
+  for (int i = 0; i < TM; ++i) fa[0][i] = DgFrag<BM, A_KMAJOR>::read(smem, wm * WM + i * 32, 0, lane);
+
+  constexpr int NMFMA = TM * TN;
+  constexpr int NREAD = (A_KMAJOR ? TM : 2 * TM) + (B_KMAJOR ? TN : 2 * TN);
+  constexpr int RPM = (NREAD + NMFMA - 1) / NMFMA;
+  // One k-step of 16: multiply fragment set `cur` while set `cur^1` is fetched from
+  // (tile, ks_next).  The hints pin the order MFMA, LDS read, MFMA, LDS read, ... so the
+  // LDS latency hides behind the matrix pipe.
+  auto kstep = [&](auto cur_tag, const bf16* ta, int ks_next) {
+    constexpr int cur = decltype(cur_tag)::value;
+    const bf16* tb = ta + BM * DG_BK;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[cur ^ 1][j] = DgFrag<BN, B_KMAJOR>::read(tb, wn * WN + j * 32, ks_next, lane);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[cur ^ 1][i] = DgFrag<BM, A_KMAJOR>::read(ta, wm * WM + i * 32, ks_next, lane);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
+    DgInterleave<0, NMFMA, NREAD, RPM, 0>::hint();
+  };
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+
+  // Per k-tile kt (stage kt&1):
+  //   k-steps 0..2 multiply while fetching the next k-step's fragments from the same tile;
+  //   then every wave waits for its own reads and for its share of tile kt+1 to land, and
+  //   the workgroup barrier makes both facts global: tile kt's stage may now be refilled
+  //   (tile kt+2 is issued into it) and tile kt+1 may be read;
+  //   k-step 3 multiplies while fetching k-step 0 of tile kt+1 (on the last tile that is a
+  //   stale but in-bounds read whose result is never used).
+  for (int kt = 0; kt < nk; ++kt) {
+    bf16* cur = smem + (kt & 1) * STAGE_ELEMS;
+    bf16* nxt = smem + ((kt & 1) ^ 1) * STAGE_ELEMS;
+    kstep(S0{}, cur, 1);
+    kstep(S1{}, cur, 2);
+    kstep(S0{}, cur, 3);
+    __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
+    __builtin_amdgcn_s_barrier();
+    if (kt + 2 < nk) {
+      la.issue(cur, kt + 2, wave);
+      lb.issue(cur + BM * DG_BK, kt + 2, wave);
+    }
+    kstep(S1{}, nxt, 0);
+  }
+
+  // acc[i][j][r]: row m = lane%32 of the 32x32 tile, column n = 8*(r/4) + 4*(lane/32) + r%4.
+  const int frow = lane & 31, fchunk = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int64_t m = m0 + wm * WM + i * 32 + frow;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int64_t n = n0 + wn * WN + j * 32 + g * 8 + fchunk * 4;
+        float v[4] = {acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
+        mg_epilogue4<MODE>(epi, m, n, v);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// host side.  Variant ids continue the first-generation kernel's (1..4):
+//   5: 256x256 tile, 8 waves   6: 256x256, 4 waves   7: 128x128, 4 waves   8: 256x128, 4 waves
+// ---------------------------------------------------------------------------
+inline bool dg_variant_tile(int variant, MgTile* t) {
+  switch (variant) {
+    case 5: case 6: *t = {256, 256}; return true;
+    case 7: *t = {128, 128}; return true;
+    case 8: *t = {256, 128}; return true;
+    default: return false;
+  }
+}
+
+inline bool dg_shape_ok(int variant, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb) {
+  MgTile t;
+  if (!dg_variant_tile(variant, &t)) return false;
+  return M % t.bm == 0 && N % t.bn == 0 && K % DG_BK == 0 && K >= DG_BK && lda % 8 == 0 && ldb % 8 == 0 &&
+         (M / t.bm) * (N / t.bn) < (1ll << 31);
+}
+
+// Picks between the 256x256 (one workgroup per CU) and 128x128 (two per CU) tiles by the
+// number of full-chip rounds each needs; 0 if neither fits the shape.
+inline int dg_choose_variant(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb) {
+  const bool ok5 = dg_shape_ok(5, M, N, K, lda, ldb), ok7 = dg_shape_ok(7, M, N, K, lda, ldb);
+  if (!ok7) return 0;  // anything divisible by 256 is divisible by 128
+  if (!ok5) return 7;
+  const int64_t t5 = (M / 256) * (N / 256), t7 = (M / 128) * (N / 128);
+  const double cost5 = (double)((t5 + 255) / 256) * 4.0 / 1.15;
+  const double cost7 = (double)((t7 + 511) / 512) * 2.0;
+  return cost5 <= cost7 ? 5 : 7;
+}
+
+template <int BM, int BN, int WGM, int WGN, bool AK, bool BK_, int MODE>
+inline hipError_t dg_launch_one(const bf16* a, int64_t lda, const bf16* b, int64_t ldb, int64_t M, int64_t N,
+                                int64_t K, const EpiArgs<bf16>& epi, hipStream_t st) {
+  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, AK, BK_, MODE>;
+  constexpr size_t smem = (size_t)DG_STAGES * (BM + BN) * DG_BK * sizeof(bf16);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tm = (int)(M / BM), tn = (int)(N / BN);
+  static int xcd_remap = -1, group = 8;
+  if (xcd_remap < 0) {  // tuning knobs
+    const char* e1 = getenv("VARUNA_XCD_REMAP");
+    const char* e2 = getenv("VARUNA_TILE_GROUP");
+    xcd_remap = e1 ? atoi(e1) : 1;
+    group = e2 ? atoi(e2) : 8;
+    if (group < 1) group = 1;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)(tm * tn)), dim3(WGM * WGN * kWave), smem, st, a, lda, b, ldb,
+                     (int)K, tm, tn, epi, xcd_remap, group);
+  return hipGetLastError();
+}
+
+template <bool AK, bool BK_, int MODE>
+inline hipError_t dg_launch_variant(int variant, const bf16* a, int64_t lda, const bf16* b, int64_t ldb,
+                                    int64_t M, int64_t N, int64_t K, const EpiArgs<bf16>& epi, hipStream_t st) {
+  switch (variant) {
+    case 5: return dg_launch_one<256, 256, 2, 4, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, st);
+    case 6: return dg_launch_one<256, 256, 2, 2, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, st);
+    case 7: return dg_launch_one<128, 128, 2, 2, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, st);
+    case 8: return dg_launch_one<256, 128, 2, 2, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+inline hipError_t launch_gemm_dma(int op, int mode, int variant, const bf16* a, int64_t lda, const bf16* b,
+                                  int64_t ldb, int64_t M, int64_t N, int64_t K, const EpiArgs<bf16>& epi,
+                                  hipStream_t st) {
+  if (op == GEMM_FWD) {
+    if (mode == EPI_BIAS) return dg_launch_variant<true, true, EPI_BIAS>(variant, a, lda, b, ldb, M, N, K, epi, st);
+    if (mode == EPI_BIAS_GELU) return dg_launch_variant<true, true, EPI_BIAS_GELU>(variant, a, lda, b, ldb, M, N, K, epi, st);
+    if (mode == EPI_BIAS_RES) return dg_launch_variant<true, true, EPI_BIAS_RES>(variant, a, lda, b, ldb, M, N, K, epi, st);
+  } else if (op == GEMM_DGRAD) {
+    if (mode == EPI_PLAIN) return dg_launch_variant<true, false, EPI_PLAIN>(variant, a, lda, b, ldb, M, N, K, epi, st);
+    if (mode == EPI_DGELU) return dg_launch_variant<true, false, EPI_DGELU>(variant, a, lda, b, ldb, M, N, K, epi, st);
+  } else if (op == GEMM_WGRAD) {
+    if (mode == EPI_ACCUM_F32) return dg_launch_variant<false, false, EPI_ACCUM_F32>(variant, a, lda, b, ldb, M, N, K, epi, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace varuna

@@ -25,6 +25,7 @@
 #include "attention_mfma.h"
 #include "attention_simple.h"
 #include "common.h"
+#include "gemm_dma.h"
 #include "gemm_mfma.h"
 #include "gemm_simple.h"
 #include "norm_reduce.h"
@@ -196,7 +197,15 @@ template <> struct GemmDispatch<bf16> {
     const bool ptr_ok = aligned16(a) && aligned16(b) && aligned16(e.bias) && aligned16(e.aux_in) &&
                         aligned16(e.out) && aligned16(e.aux_out) && aligned16(e.out_f32) && (N % 8 == 0);
     int v = variant;
-    if (v == 0) v = ptr_ok ? mg_choose_variant(M, N, K, lda, ldb) : -1;
+    if (v == 0) {
+      v = ptr_ok ? dg_choose_variant(M, N, K, lda, ldb) : -1;
+      if (v == 0) v = mg_choose_variant(M, N, K, lda, ldb);
+      if (v == 0) v = -1;
+    }
+    if (v >= 5) {
+      if (!ptr_ok || !dg_shape_ok(v, M, N, K, lda, ldb)) return hipErrorInvalidConfiguration;
+      return launch_gemm_dma(op, mode, v, a, lda, b, ldb, M, N, K, e, s);
+    }
     if (v > 0) {
       if (!ptr_ok || !mg_shape_ok(v, M, N, K, lda, ldb)) return hipErrorInvalidConfiguration;
       return launch_gemm_mfma(op, mode, v, a, lda, b, ldb, M, N, K, e, s);

@@ -71,6 +71,8 @@ def test_gemm_bf16_simple_kernel(shape):
 @pytest.mark.parametrize("variant,shape", [
     (1, (512, 768, 256)), (2, (512, 768, 256)), (3, (512, 384, 192)), (4, (384, 640, 320)),
     (2, (256, 256, 64)), (4, (128, 128, 64)),
+    (5, (512, 768, 256)), (6, (512, 768, 256)), (7, (384, 640, 320)), (8, (512, 384, 192)),
+    (5, (256, 256, 64)), (7, (128, 128, 64)), (7, (256, 128, 128)), (6, (256, 512, 192)),
 ])
 def test_gemm_bf16_mfma_variants(variant, shape):
     """Each MFMA tile configuration on several tiles, k-steps and a single-k-step case."""

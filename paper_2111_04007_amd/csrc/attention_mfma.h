@@ -1,16 +1,450 @@
-// bf16 MFMA flash-style attention for gfx950 (forward and backward).
+// bf16 MFMA flash-style attention for gfx950: forward, and a two-kernel
+// deterministic backward (no atomics).  Head dim D in {64, 96, 128}, sequence
+// length a multiple of 128.  qkv is [b*s, 3h] (Q | K | V column blocks, head j at
+// column j*D of each), ctx / dctx are [b*s, h], lse / delta are [b, heads, s] fp32.
+//
+// All three kernels keep two 64-row tiles in LDS (rows of D values, padded pitch)
+// and hold the other operands in registers.  Products use
+// v_mfma_f32_32x32x16_bf16 whose operand layout is: row operand lane L -> row
+// L%32, k = 8*(L/32)..+7; column operand likewise; result lane L -> column L%32,
+// rows 8*(r/4) + 4*(L/32) + r%4 for the 16 registers r.  Scores are computed
+// "transposed" (tile rows as the MFMA row operand) so that a lane ends up with 16
+// scores of ONE softmax row per 32x32 block: row statistics need one cross-half
+// shuffle, and the probabilities are already laid out as the column operand of
+// the following product, whose other operand comes out of LDS through the
+// transposing read ds_read_b64_tr_b16 (the k-slot order of the two operands
+// then agrees by construction).
+//
+//   forward (per 128-query workgroup, 32 queries per wave; K, V tiles in LDS):
+//     S^T = K Q^T ; online softmax in base 2 ; O^T += V^T P^T
+//   backward dQ (same geometry): S^T, dP^T = V dO^T ; dS = P (dP - delta) ;
+//     dQ^T += K^T dS^T ; also writes delta = rowsum(dO * O)
+//   backward dK/dV (per 128-key workgroup, 32 keys per wave; Q, dO tiles in LDS):
+//     S = Q K^T, dP = dO V^T ; dV^T += dO^T P ; dK^T += Q^T dS
 #pragma once
 #include "common.h"
 
 namespace varuna {
 
-inline bool attn_mfma_supported(int s, int d) { (void)s; (void)d; return false; }
+typedef short at_shortx4 __attribute__((ext_vector_type(4)));
 
-inline hipError_t launch_attention_fwd_mfma(const bf16*, bf16*, float*, int, int, int, int, int, hipStream_t) {
+template <int D>
+struct AttnCfg {
+  static_assert(D == 64 || D == 96 || D == 128, "head dim");
+  // Row pitch in elements: pitch bytes = 13*16 (D=64) or 19*16 (D=96,128).  An odd number
+  // of 16-byte units spreads 16 consecutive rows over all banks for ds_read_b128, and
+  // 4 consecutive rows' 32-byte segments do not overlap for the transposing reads.
+  static constexpr int PITCH = (D == 64) ? 104 : 152;
+  static constexpr int CH = D / 8;             // 16-byte chunks per row
+  static constexpr int CPT = 64 * CH / 256;    // chunks per thread for a 64-row tile, 256 threads
+  static constexpr int TILE = 64 * PITCH;      // elements per LDS tile
+  static constexpr int KD = D / 16;            // k-steps over the head dim
+  static constexpr int DB = D / 32;            // 32-wide blocks of the head dim
+};
+
+// 64 x D tile: global -> registers -> LDS, 256 threads.
+template <int D>
+struct AttnTileRegs {
+  bf16x8 v[AttnCfg<D>::CPT];
+  __device__ __forceinline__ void load(const bf16* __restrict__ base, int64_t row_stride, int tid) {
+#pragma unroll
+    for (int i = 0; i < AttnCfg<D>::CPT; ++i) {
+      const int id = tid + i * 256, r = id / AttnCfg<D>::CH, c = id % AttnCfg<D>::CH;
+      v[i] = *reinterpret_cast<const bf16x8*>(base + r * row_stride + c * 8);
+    }
+  }
+  __device__ __forceinline__ void store(bf16* __restrict__ lds, int tid) const {
+#pragma unroll
+    for (int i = 0; i < AttnCfg<D>::CPT; ++i) {
+      const int id = tid + i * 256, r = id / AttnCfg<D>::CH, c = id % AttnCfg<D>::CH;
+      *reinterpret_cast<bf16x8*>(lds + r * AttnCfg<D>::PITCH + c * 8) = v[i];
+    }
+  }
+};
+
+// Row operand from an LDS tile: row (row_base + lane%32), columns col0 + 8*(lane/32) .. +7.
+template <int D>
+__device__ __forceinline__ bf16x8 at_row_frag(const bf16* tile, int row_base, int col0, int lane) {
+  return *reinterpret_cast<const bf16x8*>(tile + (row_base + (lane & 31)) * AttnCfg<D>::PITCH + col0 + 8 * (lane >> 5));
+}
+
+// Transposed row operand: operand row = tile column (col_base + lane%32); its 8 k-slots are
+// tile rows r0 + 4*(lane/32) + {0..3} and r0 + 8 + 4*(lane/32) + {0..3} -- the order in
+// which a lane holds the rows of a 32x32 MFMA result, i.e. of P / dS.
+template <int D>
+__device__ __forceinline__ bf16x8 at_tr_frag(const bf16* tile, int r0, int col_base, int lane) {
+  const int j = lane & 15;
+  const bf16* p = tile + (r0 + 4 * (lane >> 5) + (j >> 2)) * AttnCfg<D>::PITCH + col_base + ((lane >> 4) & 1) * 16 + 4 * (j & 3);
+  at_shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) at_shortx4*)p);
+  at_shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) at_shortx4*)(p + 8 * AttnCfg<D>::PITCH));
+  union { struct { at_shortx4 a, b; } s; bf16x8 v; } u;
+  u.s.a = lo; u.s.b = hi;
+  return u.v;
+}
+
+__device__ __forceinline__ bf16x8 at_pack8(const float* p) {
+  bf16x8 r;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] = (bf16)p[i];
+  return r;
+}
+
+// ---------------------------------------------------------------------------
+// forward
+// ---------------------------------------------------------------------------
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
+                                                            float* __restrict__ lse, int s, int heads,
+                                                            float scale_log2e) {
+  using C = AttnCfg<D>;
+  __shared__ __attribute__((aligned(16))) bf16 sk[C::TILE];
+  __shared__ __attribute__((aligned(16))) bf16 sv[C::TILE];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
+  const int qb = gridDim.x - 1 - blockIdx.x;  // long (late) query blocks first under the causal mask
+  const int head = blockIdx.y, bi = blockIdx.z;
+  const int h = heads * D;
+  const int64_t ld = 3 * (int64_t)h;
+  const bf16* base = qkv + (int64_t)bi * s * ld + head * D;
+  const int q0 = qb * 128, qw = q0 + wave * 32;  // this wave's first query
+  const int query = qw + (lane & 31);
+
+  bf16x8 qf[C::KD];
+#pragma unroll
+  for (int t = 0; t < C::KD; ++t)
+    qf[t] = *reinterpret_cast<const bf16x8*>(base + (int64_t)query * ld + 16 * t + 8 * hf);
+
+  floatx16 o[C::DB];
+#pragma unroll
+  for (int i = 0; i < C::DB; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  const int nkb = CAUSAL ? (q0 + 128) / 64 : s / 64;
+  AttnTileRegs<D> rk, rv;
+  rk.load(base + h, ld, tid);
+  rv.load(base + 2 * h, ld, tid);
+  for (int kb = 0; kb < nkb; ++kb) {
+    if (kb) __syncthreads();
+    rk.store(sk, tid);
+    rv.store(sv, tid);
+    __syncthreads();
+    if (kb + 1 < nkb) {
+      rk.load(base + (int64_t)(kb + 1) * 64 * ld + h, ld, tid);
+      rv.load(base + (int64_t)(kb + 1) * 64 * ld + 2 * h, ld, tid);
+    }
+    const int k0 = kb * 64;
+    if (CAUSAL && k0 > qw + 31) continue;  // whole key block is in this wave's future
+    floatx16 sc[2];
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sc[sb][r] = 0.f;
+#pragma unroll
+      for (int t = 0; t < C::KD; ++t)
+        sc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_row_frag<D>(sk, sb * 32, 16 * t, lane), qf[t], sc[sb], 0, 0, 0);
+    }
+    float p[2][16];
+    float mx = -INFINITY;
+    const bool need_mask = CAUSAL && (k0 + 63 > qw);
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = sc[sb][r] * scale_log2e;
+        if (need_mask) {
+          const int key = k0 + sb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+          if (key > query) v = -INFINITY;
+        }
+        p[sb][r] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx);           // finite: key 0 is visible to every query
+    const float alpha = exp2f(m - m_new);
+    m = m_new;
+    float psum = 0.f;
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        p[sb][r] = exp2f(p[sb][r] - m_new);
+        psum += p[sb][r];
+      }
+    l = l * alpha + psum;
+#pragma unroll
+    for (int i = 0; i < C::DB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 pf = at_pack8(&p[sb][8 * t]);
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db)
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_tr_frag<D>(sv, sb * 32 + 16 * t, db * 32, lane), pf, o[db], 0, 0, 0);
+      }
+  }
+  l += __shfl_xor(l, 32, 64);
+  const float inv = 1.0f / l;
+  if (lse && hf == 0) lse[((int64_t)bi * heads + head) * s + query] = (m + log2f(l)) * 0.6931471805599453f;
+  bf16* crow = ctx + ((int64_t)bi * s + query) * h + head * D;
+#pragma unroll
+  for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[db][4 * g + e] * inv);
+      *reinterpret_cast<bf16x4*>(crow + db * 32 + 8 * g + 4 * hf) = v;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// backward, query side: dQ and delta
+// ---------------------------------------------------------------------------
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
+                                                               const float* __restrict__ lse,
+                                                               const bf16* __restrict__ dctx, bf16* __restrict__ dqkv,
+                                                               float* __restrict__ delta, int s, int heads,
+                                                               float scale, float scale_log2e) {
+  using C = AttnCfg<D>;
+  __shared__ __attribute__((aligned(16))) bf16 sk[C::TILE];
+  __shared__ __attribute__((aligned(16))) bf16 sv[C::TILE];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
+  const int qb = gridDim.x - 1 - blockIdx.x;
+  const int head = blockIdx.y, bi = blockIdx.z;
+  const int h = heads * D;
+  const int64_t ld = 3 * (int64_t)h;
+  const bf16* base = qkv + (int64_t)bi * s * ld + head * D;
+  const int q0 = qb * 128, qw = q0 + wave * 32;
+  const int query = qw + (lane & 31);
+  const int64_t orow = ((int64_t)bi * s + query) * h + head * D;
+  const int64_t sidx = ((int64_t)bi * heads + head) * s + query;
+
+  bf16x8 qf[C::KD], gf[C::KD];
+  float dl = 0.f;
+#pragma unroll
+  for (int t = 0; t < C::KD; ++t) {
+    qf[t] = *reinterpret_cast<const bf16x8*>(base + (int64_t)query * ld + 16 * t + 8 * hf);
+    gf[t] = *reinterpret_cast<const bf16x8*>(dctx + orow + 16 * t + 8 * hf);
+    const bf16x8 of = *reinterpret_cast<const bf16x8*>(ctx + orow + 16 * t + 8 * hf);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dl += (float)gf[t][e] * (float)of[e];
+  }
+  dl += __shfl_xor(dl, 32, 64);
+  if (hf == 0) delta[sidx] = dl;
+  const float l2 = lse[sidx] * 1.4426950408889634f;  // log-sum-exp in base 2
+
+  floatx16 dq[C::DB];
+#pragma unroll
+  for (int i = 0; i < C::DB; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dq[i][r] = 0.f;
+
+  const int nkb = CAUSAL ? (q0 + 128) / 64 : s / 64;
+  AttnTileRegs<D> rk, rv;
+  rk.load(base + h, ld, tid);
+  rv.load(base + 2 * h, ld, tid);
+  for (int kb = 0; kb < nkb; ++kb) {
+    if (kb) __syncthreads();
+    rk.store(sk, tid);
+    rv.store(sv, tid);
+    __syncthreads();
+    if (kb + 1 < nkb) {
+      rk.load(base + (int64_t)(kb + 1) * 64 * ld + h, ld, tid);
+      rv.load(base + (int64_t)(kb + 1) * 64 * ld + 2 * h, ld, tid);
+    }
+    const int k0 = kb * 64;
+    if (CAUSAL && k0 > qw + 31) continue;
+    const bool need_mask = CAUSAL && (k0 + 63 > qw);
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+      floatx16 sc, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int t = 0; t < C::KD; ++t) {
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_row_frag<D>(sk, sb * 32, 16 * t, lane), qf[t], sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_row_frag<D>(sv, sb * 32, 16 * t, lane), gf[t], dp, 0, 0, 0);
+      }
+      float ds[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float pr = exp2f(sc[r] * scale_log2e - l2);
+        if (need_mask) {
+          const int key = k0 + sb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+          if (key > query) pr = 0.f;
+        }
+        ds[r] = pr * (dp[r] - dl);
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 df = at_pack8(&ds[8 * t]);
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db)
+          dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_tr_frag<D>(sk, sb * 32 + 16 * t, db * 32, lane), df, dq[db], 0, 0, 0);
+      }
+    }
+  }
+  bf16* drow = dqkv + ((int64_t)bi * s + query) * ld + head * D;
+#pragma unroll
+  for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (bf16)(dq[db][4 * g + e] * scale);
+      *reinterpret_cast<bf16x4*>(drow + db * 32 + 8 * g + 4 * hf) = v;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// backward, key side: dK and dV
+// ---------------------------------------------------------------------------
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv, const float* __restrict__ lse,
+                                                                const bf16* __restrict__ dctx,
+                                                                const float* __restrict__ delta, bf16* __restrict__ dqkv,
+                                                                int s, int heads, float scale, float scale_log2e) {
+  using C = AttnCfg<D>;
+  __shared__ __attribute__((aligned(16))) bf16 sq[C::TILE];
+  __shared__ __attribute__((aligned(16))) bf16 sg[C::TILE];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
+  const int kblk = blockIdx.x;  // early key blocks (most queries under the causal mask) first
+  const int head = blockIdx.y, bi = blockIdx.z;
+  const int h = heads * D;
+  const int64_t ld = 3 * (int64_t)h;
+  const bf16* base = qkv + (int64_t)bi * s * ld + head * D;
+  const bf16* gbase = dctx + (int64_t)bi * s * h + head * D;
+  const int kb0 = kblk * 128, kw = kb0 + wave * 32;  // this wave's first key
+  const int key = kw + (lane & 31);
+  const int64_t sbase = ((int64_t)bi * heads + head) * s;
+
+  bf16x8 kf[C::KD], vf[C::KD];
+#pragma unroll
+  for (int t = 0; t < C::KD; ++t) {
+    kf[t] = *reinterpret_cast<const bf16x8*>(base + (int64_t)key * ld + h + 16 * t + 8 * hf);
+    vf[t] = *reinterpret_cast<const bf16x8*>(base + (int64_t)key * ld + 2 * h + 16 * t + 8 * hf);
+  }
+  floatx16 dk[C::DB], dv[C::DB];
+#pragma unroll
+  for (int i = 0; i < C::DB; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
+
+  const int qs = CAUSAL ? kb0 / 64 : 0, nqb = s / 64;
+  AttnTileRegs<D> rq, rg;
+  rq.load(base + (int64_t)qs * 64 * ld, ld, tid);
+  rg.load(gbase + (int64_t)qs * 64 * h, h, tid);
+  for (int qb = qs; qb < nqb; ++qb) {
+    if (qb > qs) __syncthreads();
+    rq.store(sq, tid);
+    rg.store(sg, tid);
+    __syncthreads();
+    if (qb + 1 < nqb) {
+      rq.load(base + (int64_t)(qb + 1) * 64 * ld, ld, tid);
+      rg.load(gbase + (int64_t)(qb + 1) * 64 * h, h, tid);
+    }
+    const int q0 = qb * 64;
+    if (CAUSAL && q0 + 63 < kw) continue;  // every query of the block precedes this wave's keys
+    const bool need_mask = CAUSAL && (q0 < kw + 31);
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+      floatx16 sc, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int t = 0; t < C::KD; ++t) {
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_row_frag<D>(sq, sb * 32, 16 * t, lane), kf[t], sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_row_frag<D>(sg, sb * 32, 16 * t, lane), vf[t], dp, 0, 0, 0);
+      }
+      float pr[16], ds[16];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int qi = q0 + sb * 32 + 8 * g + 4 * hf;  // 4 consecutive queries
+        const floatx4 l4 = *reinterpret_cast<const floatx4*>(lse + sbase + qi);
+        const floatx4 d4 = *reinterpret_cast<const floatx4*>(delta + sbase + qi);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * g + e;
+          float p = exp2f(sc[r] * scale_log2e - l4[e] * 1.4426950408889634f);
+          if (need_mask && (qi + e < key)) p = 0.f;
+          pr[r] = p;
+          ds[r] = p * (dp[r] - d4[e]);
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 pf = at_pack8(&pr[8 * t]);
+        const bf16x8 df = at_pack8(&ds[8 * t]);
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db) {
+          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_tr_frag<D>(sg, sb * 32 + 16 * t, db * 32, lane), pf, dv[db], 0, 0, 0);
+          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_tr_frag<D>(sq, sb * 32 + 16 * t, db * 32, lane), df, dk[db], 0, 0, 0);
+        }
+      }
+    }
+  }
+  bf16* krow = dqkv + ((int64_t)bi * s + key) * ld + h + head * D;
+  bf16* vrow = krow + h;
+#pragma unroll
+  for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 a, c;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { a[e] = (bf16)(dk[db][4 * g + e] * scale); c[e] = (bf16)dv[db][4 * g + e]; }
+      *reinterpret_cast<bf16x4*>(krow + db * 32 + 8 * g + 4 * hf) = a;
+      *reinterpret_cast<bf16x4*>(vrow + db * 32 + 8 * g + 4 * hf) = c;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+inline bool attn_mfma_supported(int s, int d) { return (d == 64 || d == 96 || d == 128) && s >= 128 && s % 128 == 0; }
+
+template <int D>
+inline hipError_t attn_fwd_mfma_d(const bf16* qkv, bf16* ctx, float* lse, int b, int s, int heads, int causal, hipStream_t st) {
+  dim3 grid((unsigned)(s / 128), (unsigned)heads, (unsigned)b);
+  const float sl = 1.4426950408889634f / sqrtf((float)D);
+  if (causal) hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, true>), grid, dim3(256), 0, st, qkv, ctx, lse, s, heads, sl);
+  else hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, false>), grid, dim3(256), 0, st, qkv, ctx, lse, s, heads, sl);
+  return hipGetLastError();
+}
+
+inline hipError_t launch_attention_fwd_mfma(const bf16* qkv, bf16* ctx, float* lse, int b, int s, int heads, int d,
+                                            int causal, hipStream_t st) {
+  if (d == 64) return attn_fwd_mfma_d<64>(qkv, ctx, lse, b, s, heads, causal, st);
+  if (d == 96) return attn_fwd_mfma_d<96>(qkv, ctx, lse, b, s, heads, causal, st);
+  if (d == 128) return attn_fwd_mfma_d<128>(qkv, ctx, lse, b, s, heads, causal, st);
   return hipErrorInvalidConfiguration;
 }
-inline hipError_t launch_attention_bwd_mfma(const bf16*, const bf16*, const float*, const bf16*, bf16*, float*, int, int,
-                                            int, int, int, hipStream_t) {
+
+template <int D>
+inline hipError_t attn_bwd_mfma_d(const bf16* qkv, const bf16* ctx, const float* lse, const bf16* dctx, bf16* dqkv,
+                                  float* delta, int b, int s, int heads, int causal, hipStream_t st) {
+  dim3 grid((unsigned)(s / 128), (unsigned)heads, (unsigned)b);
+  const float sc = 1.0f / sqrtf((float)D), sl = 1.4426950408889634f * sc;
+  if (causal) {
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, true>), grid, dim3(256), 0, st, qkv, ctx, lse, dctx, dqkv, delta, s, heads, sc, sl);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<D, true>), grid, dim3(256), 0, st, qkv, lse, dctx, delta, dqkv, s, heads, sc, sl);
+  } else {
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, false>), grid, dim3(256), 0, st, qkv, ctx, lse, dctx, dqkv, delta, s, heads, sc, sl);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<D, false>), grid, dim3(256), 0, st, qkv, lse, dctx, delta, dqkv, s, heads, sc, sl);
+  }
+  return hipGetLastError();
+}
+
+inline hipError_t launch_attention_bwd_mfma(const bf16* qkv, const bf16* ctx, const float* lse, const bf16* dctx,
+                                            bf16* dqkv, float* delta, int b, int s, int heads, int d, int causal,
+                                            hipStream_t st) {
+  if (d == 64) return attn_bwd_mfma_d<64>(qkv, ctx, lse, dctx, dqkv, delta, b, s, heads, causal, st);
+  if (d == 96) return attn_bwd_mfma_d<96>(qkv, ctx, lse, dctx, dqkv, delta, b, s, heads, causal, st);
+  if (d == 128) return attn_bwd_mfma_d<128>(qkv, ctx, lse, dctx, dqkv, delta, b, s, heads, causal, st);
   return hipErrorInvalidConfiguration;
 }
 

@@ -169,3 +169,20 @@ def test_attention_fp32(b, s, heads, d, causal):
 @pytest.mark.parametrize("b,s,heads,d,causal", [(2, 128, 2, 64, 1), (1, 200, 2, 96, 0), (1, 256, 1, 128, 1)])
 def test_attention_bf16_simple(b, s, heads, d, causal):
     run_attention_case("bf16", b, s, heads, d, causal, variant=-1)
+
+
+@pytest.mark.parametrize("b,s,heads,d,causal", [
+    (2, 128, 2, 64, 1), (1, 256, 2, 64, 0), (1, 384, 1, 96, 1), (2, 256, 1, 96, 0),
+    (1, 256, 2, 128, 1), (1, 128, 1, 128, 0), (1, 512, 1, 128, 1),
+])
+def test_attention_bf16_mfma(b, s, heads, d, causal):
+    """MFMA kernels: every head dim, causal and bidirectional, 1 to 4 query/key blocks."""
+    run_attention_case("bf16", b, s, heads, d, causal, variant=1, seed=30 + d)
+
+
+def test_attention_mfma_rejects_unsupported_shape():
+    qkv = rnd((100, 3 * 64), "bf16", 1)
+    ctx = torch.empty((100, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.VarunaError) as ei:
+        B.op_attention_fwd(qkv, ctx, None, 1, 100, 1, 64, 1, variant=1)
+    assert ei.value.code == B.EUNSUPPORTED

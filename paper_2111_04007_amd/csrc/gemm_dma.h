@@ -36,6 +36,7 @@ typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 // s_waitcnt immediates (gfx9 encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8]).
 #define DG_WAIT_VM(n) (((n) & 0xf) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 #define DG_WAIT_VM0_LGKM0 (7 << 4)
+#define DG_WAIT_LGKM0 (0xf | (3 << 14) | (7 << 4))
 
 // Direct global->LDS staging of one operand tile (ROWS x 64).
 //   k-major  : LDS [row][64 k], 8 chunks of 16 B per row, physical chunk = c ^ ((row ^ (row >> 3)) & 7)
@@ -218,18 +219,67 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
     kstep(S1{}, nxt, 0);
   }
 
-  // acc[i][j][r]: row m = lane%32 of the 32x32 tile, column n = 8*(r/4) + 4*(lane/32) + r%4.
   const int frow = lane & 31, fchunk = lane >> 5;
+  if constexpr (MODE == EPI_ACCUM_F32) {
+    // out_f32 += acc.  Reading the old values through registers would leave only a few KB
+    // in flight per CU (the accumulators own the register file), so the old tile is
+    // streamed into the now idle LDS with the same direct loads as the operands: each wave
+    // pulls its own sub-tile in passes of 32 rows x WN floats, double-buffered, adds its
+    // accumulators and stores.  Chunks of 16 B are XOR-swizzled by the row so that 16 lanes
+    // reading one column of 16 rows hit distinct banks.
+    constexpr int CPR = WN / 4;                 // 16-byte chunks per row of the pass block
+    constexpr int PASS_BYTES = 32 * WN * 4;
+    constexpr int NINS = PASS_BYTES / 1024;     // direct loads per pass
+    static_assert(NW * 2 * PASS_BYTES <= DG_STAGES * STAGE_ELEMS * 2, "epilogue staging must fit the operand stages");
+    __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
+    __builtin_amdgcn_s_barrier();               // every wave is done with the operand stages
+    unsigned char* mybuf = dg_smem + wave * (2 * PASS_BYTES);
+    float* cbase = epi.out_f32 + (m0 + wm * WM) * epi.ldc + n0 + wn * WN;
+    auto issue_pass = [&](int pass) {
+      unsigned char* buf = mybuf + (pass & 1) * PASS_BYTES;
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int64_t m = m0 + wm * WM + i * 32 + frow;
+      for (int q = 0; q < NINS; ++q) {
+        const int slot = q * 64 + lane, row = slot / CPR, pc = slot % CPR;
+        const int c = pc ^ (row & 15);
+        __builtin_amdgcn_global_load_lds((glb_ptr_t)(cbase + (int64_t)(pass * 32 + row) * epi.ldc + c * 4),
+                                         (lds_ptr_t)(buf + q * 1024), 16, 0, 0);
+      }
+    };
+    issue_pass(0);
+    if (TM > 1) issue_pass(1);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+    for (int i = 0; i < TM; ++i) {
+      if (i + 1 < TM) __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(NINS)); else __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(0));
+      const unsigned char* buf = mybuf + (i & 1) * PASS_BYTES;
+      float* crow = cbase + (int64_t)(i * 32 + frow) * epi.ldc;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int64_t n = n0 + wn * WN + j * 32 + g * 8 + fchunk * 4;
-        float v[4] = {acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
-        mg_epilogue4<MODE>(epi, m, n, v);
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int c = j * 8 + g * 2 + fchunk;
+          floatx4 v = *reinterpret_cast<const floatx4*>(buf + frow * (WN * 4) + ((c ^ (frow & 15)) << 4));
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += acc[i][j][g * 4 + e];
+          *reinterpret_cast<floatx4*>(crow + c * 4) = v;
+        }
+      if (i + 2 < TM) {
+        __builtin_amdgcn_s_waitcnt(DG_WAIT_LGKM0);  // this buffer's LDS reads are done before it is refilled
+        issue_pass(i + 2);
+      }
+    }
+  } else {
+    // acc[i][j][r]: row m = lane%32 of the 32x32 tile, column n = 8*(r/4) + 4*(lane/32) + r%4.
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int64_t m = m0 + wm * WM + i * 32 + frow;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int64_t n = n0 + wn * WN + j * 32 + g * 8 + fchunk * 4;
+          float v[4] = {acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
+          mg_epilogue4<MODE>(epi, m, n, v);
+        }
       }
     }
   }
@@ -317,6 +367,7 @@ inline hipError_t launch_gemm_dma(int op, int mode, int variant, const bf16* a, 
     if (mode == EPI_DGELU) return dg_launch_variant<true, false, EPI_DGELU>(variant, a, lda, b, ldb, M, N, K, epi, st);
   } else if (op == GEMM_WGRAD) {
     if (mode == EPI_ACCUM_F32) return dg_launch_variant<false, false, EPI_ACCUM_F32>(variant, a, lda, b, ldb, M, N, K, epi, st);
+    if (mode == EPI_PLAIN) return dg_launch_variant<false, false, EPI_PLAIN>(variant, a, lda, b, ldb, M, N, K, epi, st);
   }
   return hipErrorInvalidValue;
 }

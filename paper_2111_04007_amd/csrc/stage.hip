@@ -594,6 +594,7 @@ varuna_status_t varuna_op_gemm(int32_t dtype, int32_t op, int32_t epi, int32_t v
   if (op == GEMM_FWD && epi >= 0 && epi <= 2) mode = epi;
   else if (op == GEMM_DGRAD && (epi == 0 || epi == 3)) mode = epi == 0 ? EPI_PLAIN : EPI_DGELU;
   else if (op == GEMM_WGRAD && epi == 0) mode = EPI_ACCUM_F32;
+  else if (op == GEMM_WGRAD && epi == 4 && dtype == VARUNA_BF16 && variant >= 5) mode = EPI_PLAIN;  // tuning aid: no accumulate
   else return fail(VARUNA_EINVAL, "unknown op/epilogue combination %d/%d", op, epi);
   if (op == GEMM_FWD && !bias) return fail(VARUNA_EINVAL, "forward GEMM needs a bias");
   if ((mode == EPI_BIAS_RES || mode == EPI_DGELU) && !aux_in) return fail(VARUNA_EINVAL, "epilogue needs aux_in");

@@ -42,7 +42,7 @@ def cpu_baseline(cfg):
     except Exception:
         threads = os.cpu_count() or 1
     h, f = cfg.hidden, cfg.mlp_hidden
-    budget = 1.0e12  # FLOPs of fp64 work to aim for
+    budget = 8.0e12  # FLOPs of fp64 work to aim for (about 10-20 s on 16 cores)
     per_token = 3.0 * 2.0 * h * (4 * h + 2 * f)
     s = cfg.seq_len
     while s > 64 and per_token * s * cfg.micro_batch > budget:

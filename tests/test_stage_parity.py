@@ -64,6 +64,49 @@ def test_c2_bert_large_shaped_two_microbatches():
     _run(CONFIGS["C2"].replace(n_micro_batches=2), n_mb=2, perturb=0.0)
 
 
+def test_c3_gpt2_2p5b_shaped_two_microbatches():
+    """Config 3 at full shape (4 layers, h=1920, d=96, s=1024, b=4), M_parity = 2."""
+    _run(CONFIGS["C3"].replace(n_micro_batches=2), n_mb=2, perturb=0.0)
+
+
+def test_c4_gpt_8p3b_shaped_two_microbatches():
+    """Config 4 at full shape (3 layers, h=3072, d=96, s=1024, b=2), M_parity = 2."""
+    _run(CONFIGS["C4"].replace(n_micro_batches=2), n_mb=2, perturb=0.0)
+
+
+def test_c5_200b_class_one_microbatch():
+    """Config 5 (the benchmarked workload) at full shape and in the launch configuration
+    bench.py times (2 layers, h=8192, d=128, s=2048, b=1); one micro-batch against the
+    oracle (about 21 TFLOP of fp64 work on the host)."""
+    _run(CONFIGS["C5"].replace(n_micro_batches=1), n_mb=1, perturb=0.0)
+
+
+def test_c5_accumulation_linearity_on_gpu():
+    """fp32 accumulators at full C5 shape: gradients after 3 distinct micro-batches equal
+    the sum of three single-micro-batch runs (rel-L2 <= 1e-6)."""
+    cfg = CONFIGS["C5"].replace(n_micro_batches=3)
+    params, xs, dys = synth.device_random_stage(cfg, "cuda:0", 3)
+    st = B.Stage(cfg, "cuda:0", params_flat=params)
+    y = torch.empty_like(xs[0])
+    dx = torch.empty_like(xs[0])
+
+    def run(ms):
+        st.grad_accum_reset()
+        for m in ms:
+            st.forward(m, xs[m], y)
+        for m in ms:
+            st.backward_recompute(m, dys[m], dx)
+        torch.cuda.synchronize()
+        return st.grads.double()
+
+    total = run([0, 1, 2])
+    parts = run([0]) + run([1]) + run([2])
+    err = float((total - parts).norm() / parts.norm())
+    print(f"\nC5 accumulation linearity rel-L2 {err:.3e}", flush=True)
+    assert err <= 1e-6
+    st.close()
+
+
 def test_recompute_equals_stored_bitwise():
     """The activations re-derived by backward_recompute are bit-identical to those a
     storing forward produced (same kernels, same launch geometry)."""

@@ -169,6 +169,14 @@ def main():
                         "unit": "GB/s", "frac": ach / (flops.MI355X_HBM_PEAK / 1e9), "traffic": None,
                         "avg_launch_ms": v["ms"] / v["launches"], "launches": v["launches"] // args.steps}
 
+    # HBM traffic of the dominant kernel class from the committed rocprofv3 --pmc summary
+    if roofline is not None:
+        try:
+            with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
+                roofline["traffic"] = json.load(fh)[cfg.name][roofline["kernel"]]["hbm_bytes_per_launch"]
+        except (OSError, KeyError, ValueError):
+            roofline["traffic"] = None
+
     cpu = None if args.no_cpu_baseline else cpu_baseline(cfg)
 
     out = {

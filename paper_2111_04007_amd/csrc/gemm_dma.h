@@ -268,19 +268,41 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
       }
     }
   } else {
-    // acc[i][j][r]: row m = lane%32 of the 32x32 tile, column n = 8*(r/4) + 4*(lane/32) + r%4.
+    // bf16 outputs.  acc[i][j][r] is row m = lane%32 of the 32x32 tile, column
+    // n = 8*(r/4) + 4*(lane/32) + r%4: storing straight from that layout writes 8-byte
+    // pieces of many rows per instruction and was measured to amplify HBM write traffic
+    // 2-3x.  Instead each wave transposes its sub-tile through the idle LDS, 32 rows at a
+    // time (fp32, chunk-XOR-swizzled), and re-reads it with consecutive lanes along a row,
+    // so bias / residual / pre-GeLU reads and all stores are 16 bytes per lane and whole
+    // 128-byte lines per row.
+    constexpr int ROWB = WN * 4;              // bytes per staged fp32 row
+    constexpr int LPR = WN / 8;               // lanes per output row (8 columns each)
+    constexpr int RPI = 64 / LPR;             // rows per store instruction
+    static_assert(NW * 32 * ROWB <= DG_STAGES * STAGE_ELEMS * 2, "epilogue staging must fit the operand stages");
+    __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
+    __builtin_amdgcn_s_barrier();             // every wave is done with the operand stages
+    unsigned char* buf = dg_smem + wave * (32 * ROWB);
+    const int rrow = lane / LPR, rcol = (lane % LPR) * 8;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      const int64_t m = m0 + wm * WM + i * 32 + frow;
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int64_t n = n0 + wn * WN + j * 32 + g * 8 + fchunk * 4;
-          float v[4] = {acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
-          mg_epilogue4<MODE>(epi, m, n, v);
+          const int c = j * 8 + g * 2 + fchunk;
+          floatx4 v = {acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
+          *reinterpret_cast<floatx4*>(buf + frow * ROWB + (((c & ~15) | ((c ^ frow) & 15)) << 4)) = v;
         }
+      __builtin_amdgcn_s_waitcnt(DG_WAIT_LGKM0);  // own writes landed (the buffer is private to the wave)
+#pragma unroll
+      for (int sub = 0; sub < 32 / RPI; ++sub) {
+        const int r = sub * RPI + rrow, c0 = rcol / 4;
+        const floatx4 lo = *reinterpret_cast<const floatx4*>(buf + r * ROWB + (((c0 & ~15) | ((c0 ^ r) & 15)) << 4));
+        const floatx4 hi = *reinterpret_cast<const floatx4*>(buf + r * ROWB + ((((c0 + 1) & ~15) | (((c0 + 1) ^ r) & 15)) << 4));
+        float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        mg_epilogue8<MODE>(epi, m0 + wm * WM + i * 32 + r, n0 + wn * WN + rcol, v);
       }
+      __builtin_amdgcn_s_waitcnt(DG_WAIT_LGKM0);  // reads done before the next pass overwrites
     }
   }
 }

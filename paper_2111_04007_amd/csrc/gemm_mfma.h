@@ -76,6 +76,44 @@ __device__ __forceinline__ void mg_epilogue4(const EpiArgs<bf16>& e, int64_t m, 
   *reinterpret_cast<bf16x4*>(e.out + idx) = ov;
 }
 
+// Eight consecutive columns of one output row.
+template <int MODE>
+__device__ __forceinline__ void mg_epilogue8(const EpiArgs<bf16>& e, int64_t m, int64_t n, const float* acc) {
+  const int64_t idx = m * e.ldc + n;
+  float o[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = acc[i];
+  if (MODE == EPI_BIAS || MODE == EPI_BIAS_GELU || MODE == EPI_BIAS_RES) {
+    const bf16x8 bv = *reinterpret_cast<const bf16x8*>(e.bias + n);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] += (float)bv[i];
+  }
+  if (MODE == EPI_BIAS_GELU) {
+    if (e.aux_out) {
+      bf16x8 uv;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) uv[i] = (bf16)o[i];
+      *reinterpret_cast<bf16x8*>(e.aux_out + idx) = uv;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = gelu_tanh_f(o[i]);
+  }
+  if (MODE == EPI_BIAS_RES) {
+    const bf16x8 rv = *reinterpret_cast<const bf16x8*>(e.aux_in + idx);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] += (float)rv[i];
+  }
+  if (MODE == EPI_DGELU) {
+    const bf16x8 uv = *reinterpret_cast<const bf16x8*>(e.aux_in + idx);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] *= gelu_tanh_grad_f((float)uv[i]);
+  }
+  bf16x8 ov;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ov[i] = (bf16)o[i];
+  *reinterpret_cast<bf16x8*>(e.out + idx) = ov;
+}
+
 // Global -> register staging of one ROWS x 64 operand tile, and register -> LDS.
 // The transposing path (operand not k-major in memory) gives each thread blocks
 // of KB k-rows x 8 tile-rows: KB 16-byte loads, a register transpose, then 8

@@ -93,7 +93,7 @@ __device__ __forceinline__ bf16x8 at_pack8(const float* p) {
 // forward
 // ---------------------------------------------------------------------------
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
                                                             float* __restrict__ lse, int s, int heads,
                                                             float scale_log2e) {
   using C = AttnCfg<D>;
@@ -161,14 +161,14 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
       }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m, mx);           // finite: key 0 is visible to every query
-    const float alpha = exp2f(m - m_new);
+    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
     m = m_new;
     float psum = 0.f;
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        p[sb][r] = exp2f(p[sb][r] - m_new);
+        p[sb][r] = __builtin_amdgcn_exp2f(p[sb][r] - m_new);
         psum += p[sb][r];
       }
     l = l * alpha + psum;
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
 // backward, query side: dQ and delta
 // ---------------------------------------------------------------------------
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
                                                                const float* __restrict__ lse,
                                                                const bf16* __restrict__ dctx, bf16* __restrict__ dqkv,
                                                                float* __restrict__ delta, int s, int heads,
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
       float ds[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float pr = exp2f(sc[r] * scale_log2e - l2);
+        float pr = __builtin_amdgcn_exp2f(sc[r] * scale_log2e - l2);
         if (need_mask) {
           const int key = k0 + sb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
           if (key > query) pr = 0.f;
@@ -370,7 +370,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * g + e;
-          float p = exp2f(sc[r] * scale_log2e - l4[e] * 1.4426950408889634f);
+          float p = __builtin_amdgcn_exp2f(sc[r] * scale_log2e - l4[e] * 1.4426950408889634f);
           if (need_mask && (qi + e < key)) p = 0.f;
           pr[r] = p;
           ds[r] = p * (dp[r] - d4[e]);

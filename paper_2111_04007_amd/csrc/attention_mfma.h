@@ -335,18 +335,30 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
 
+  // Per 64-query tile the statistics lse (scaled to base 2) and delta ride along with the
+  // Q / dO tiles: threads 0..63 prefetch lse, 64..127 delta, into registers and then LDS,
+  // so the inner loop never waits on a global load.
+  __shared__ __attribute__((aligned(16))) float sstat[2][64];
   const int qs = CAUSAL ? kb0 / 64 : 0, nqb = s / 64;
   AttnTileRegs<D> rq, rg;
+  float rstat = 0.f;
+  auto load_stat = [&](int qb) {
+    if (tid < 64) rstat = lse[sbase + qb * 64 + tid] * 1.4426950408889634f;
+    else if (tid < 128) rstat = delta[sbase + qb * 64 + tid - 64];
+  };
   rq.load(base + (int64_t)qs * 64 * ld, ld, tid);
   rg.load(gbase + (int64_t)qs * 64 * h, h, tid);
+  load_stat(qs);
   for (int qb = qs; qb < nqb; ++qb) {
     if (qb > qs) __syncthreads();
     rq.store(sq, tid);
     rg.store(sg, tid);
+    if (tid < 128) sstat[tid >> 6][tid & 63] = rstat;
     __syncthreads();
     if (qb + 1 < nqb) {
       rq.load(base + (int64_t)(qb + 1) * 64 * ld, ld, tid);
       rg.load(gbase + (int64_t)(qb + 1) * 64 * h, h, tid);
+      load_stat(qb + 1);
     }
     const int q0 = qb * 64;
     if (CAUSAL && q0 + 63 < kw) continue;  // every query of the block precedes this wave's keys
@@ -364,14 +376,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
       float pr[16], ds[16];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int qi = q0 + sb * 32 + 8 * g + 4 * hf;  // 4 consecutive queries
-        const floatx4 l4 = *reinterpret_cast<const floatx4*>(lse + sbase + qi);
-        const floatx4 d4 = *reinterpret_cast<const floatx4*>(delta + sbase + qi);
+        const int ql = sb * 32 + 8 * g + 4 * hf;  // 4 consecutive queries of the tile
+        const floatx4 l4 = *reinterpret_cast<const floatx4*>(&sstat[0][ql]);
+        const floatx4 d4 = *reinterpret_cast<const floatx4*>(&sstat[1][ql]);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * g + e;
-          float p = __builtin_amdgcn_exp2f(sc[r] * scale_log2e - l4[e] * 1.4426950408889634f);
-          if (need_mask && (qi + e < key)) p = 0.f;
+          float p = __builtin_amdgcn_exp2f(sc[r] * scale_log2e - l4[e]);
+          if (need_mask && (q0 + ql + e < key)) p = 0.f;
           pr[r] = p;
           ds[r] = p * (dp[r] - d4[e]);
         }

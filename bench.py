@@ -26,6 +26,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="C5", help="C1..C5 (default: the largest stage, C5)")
     ap.add_argument("--micro-batches", type=int, default=0, help="override M (default: the config's)")
+    ap.add_argument("--wgrad-group", type=int, default=4,
+                    help="micro-batches per weight-gradient GEMM (library knob; 1 = per micro-batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
     return ap.parse_args()
@@ -84,6 +86,7 @@ def main():
     cfg = CONFIGS[args.config]
     if args.micro_batches:
         cfg = cfg.replace(n_micro_batches=args.micro_batches)
+    cfg = cfg.replace(wgrad_group=max(1, args.wgrad_group))
     M = cfg.n_micro_batches
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -101,6 +104,7 @@ def main():
             st.forward(m, xs[m], ys[m], stream)
         for m in range(M):
             st.backward_recompute(m, dys[m], dxs[m], stream)
+        st.grad_flush(stream)
 
     for _ in range(args.warmup):
         step()
@@ -122,6 +126,7 @@ def main():
     ev[1].record(stream)
     for m in range(M):
         st.backward_recompute(m, dys[m], dxs[m], stream)
+    st.grad_flush(stream)
     ev[2].record(stream)
     torch.cuda.synchronize()
     ms_f = ev[0].elapsed_time(ev[1]) / M
@@ -149,6 +154,8 @@ def main():
             for m in range(M):
                 st.backward_recompute(m, dys[m], dxs[m], stream)
                 _acc(tot, st.profile_collect())
+            st.grad_flush(stream)
+            _acc(tot, st.profile_collect())
         st.profile_enable(False)
         classes = {k: {"ms_per_step": v["ms"] / args.steps, "launches_per_step": v["launches"] // args.steps,
                        "tflops": (v["flops"] / (v["ms"] * 1e-3) / 1e12) if v["ms"] > 0 and v["flops"] > 0 else None,
@@ -187,7 +194,7 @@ def main():
         "config": {
             "workload": cfg.name, "n_layers": cfg.n_layers, "hidden": cfg.hidden, "n_heads": cfg.n_heads,
             "seq_len": cfg.seq_len, "micro_batch": cfg.micro_batch, "n_micro_batches": M,
-            "mlp_hidden": cfg.mlp_hidden, "causal": cfg.causal,
+            "mlp_hidden": cfg.mlp_hidden, "causal": cfg.causal, "wgrad_group": cfg.wgrad_group,
             "ms_per_micro_batch": ms_mb, "ms_forward_per_micro_batch": ms_f,
             "ms_recompute_backward_per_micro_batch": ms_rb,
             "frac_of_bf16_mfma_peak": frac_peak, "peak_tflops_used": flops.MI355X_BF16_DENSE_PEAK / 1e12,

@@ -78,6 +78,8 @@ typedef struct {
   int32_t causal;          /* 1: key index <= query index only; 0: bidirectional */
   int32_t dtype;           /* varuna_dtype_t */
   float ln_eps;            /* 0 means 1e-5 */
+  int32_t wgrad_group;     /* G: weight-gradient GEMMs are issued once per G micro-batches with
+                              reduction length G*T (0 or 1: after every micro-batch) */
 } varuna_stage_config_t;
 
 /* Byte sizes of the four caller-allocated device buffers for this configuration.
@@ -111,14 +113,26 @@ varuna_status_t varuna_stage_forward(varuna_stage_t* st, int32_t mb, const void*
 /* Recompute + backward for slot mb: re-derives all internal activations from
  * boundary slot mb (bit-identical to what forward computed), then from the
  * upstream gradient dy_in [T,h] writes the input gradient dx_out [T,h] and adds
- * this micro-batch's parameter gradients into grads_f32.  Requires a forward of
+ * this micro-batch's parameter gradients into grads_f32 (the four matrix gradients
+ * per layer possibly deferred, see varuna_stage_grad_flush).  Requires a forward of
  * slot mb since that slot was last consumed (else VARUNA_ESTATE).  Calls for
  * different slots may be interleaved with forwards in any order. */
 varuna_status_t varuna_stage_backward_recompute(varuna_stage_t* st, int32_t mb,
                                                 const void* dy_in /*device*/,
                                                 void* dx_out /*device*/, void* hip_stream);
 
-/* Zero-fills grads_f32 (start of a mini-batch). */
+/* With wgrad_group G > 1 the operands of the weight-gradient products dW += dY^T X are kept
+ * for up to G micro-batches (the workspace holds G slots of them, stacked along the token
+ * dimension) and each dW receives ONE GEMM over G*T tokens and one fp32 read-modify-write:
+ * gradient accumulation within a GPU (Job Morphing, "Correctness-preserving morphing") with
+ * the accumulation partly folded into the GEMM's reduction.  The matrix gradients are then
+ * complete only after every G-th backward_recompute call, or after this call, which issues
+ * the GEMMs for whatever has been gathered (a no-op when nothing is pending or G <= 1).
+ * Bias, gamma and beta gradients are always added per call.  Call it before reading
+ * grads_f32 at the end of a mini-batch. */
+varuna_status_t varuna_stage_grad_flush(varuna_stage_t* st, void* hip_stream);
+
+/* Zero-fills grads_f32 (start of a mini-batch) and drops any gathered, unflushed operands. */
 varuna_status_t varuna_stage_grad_accum_reset(varuna_stage_t* st, void* hip_stream);
 
 /* Releases the host-side handle.  Device buffers stay with the caller. */

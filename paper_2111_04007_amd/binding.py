@@ -27,7 +27,7 @@ OP_FWD, OP_DGRAD, OP_WGRAD = 0, 1, 2
 EXPORTS = (
     "varuna_stage_query_sizes", "varuna_stage_param_offset", "varuna_stage_create",
     "varuna_stage_forward", "varuna_stage_backward_recompute", "varuna_stage_grad_accum_reset",
-    "varuna_stage_destroy", "varuna_last_error", "varuna_stage_debug_forward_save",
+    "varuna_stage_grad_flush", "varuna_stage_destroy", "varuna_last_error", "varuna_stage_debug_forward_save",
     "varuna_stage_debug_saved_region", "varuna_stage_profile_enable", "varuna_stage_profile_collect",
     "varuna_op_gemm", "varuna_op_layernorm_fwd", "varuna_op_layernorm_bwd", "varuna_op_colsum",
     "varuna_op_colreduce_scratch_bytes", "varuna_op_attention_fwd", "varuna_op_attention_bwd",
@@ -43,13 +43,13 @@ class VarunaError(RuntimeError):
 class CConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "hidden", "n_heads", "seq_len", "micro_batch", "n_micro_batches",
-        "mlp_hidden", "causal", "dtype")] + [("ln_eps", C.c_float)]
+        "mlp_hidden", "causal", "dtype")] + [("ln_eps", C.c_float), ("wgrad_group", C.c_int32)]
 
 
 def c_config(cfg: StageConfig) -> CConfig:
     return CConfig(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.seq_len, cfg.micro_batch,
                    cfg.n_micro_batches, cfg.mlp_hidden, int(cfg.causal),
-                   F32 if cfg.dtype == "f32" else BF16, cfg.ln_eps)
+                   F32 if cfg.dtype == "f32" else BF16, cfg.ln_eps, cfg.wgrad_group)
 
 
 _lib = None
@@ -75,6 +75,7 @@ def load():
         "varuna_stage_forward": (i32, [vp, i32, vp, vp, vp]),
         "varuna_stage_backward_recompute": (i32, [vp, i32, vp, vp, vp]),
         "varuna_stage_grad_accum_reset": (i32, [vp, vp]),
+        "varuna_stage_grad_flush": (i32, [vp, vp]),
         "varuna_stage_destroy": (i32, [vp]),
         "varuna_last_error": (C.c_char_p, []),
         "varuna_stage_debug_forward_save": (i32, [vp, i32, vp, vp, vp]),
@@ -184,6 +185,9 @@ class Stage:
 
     def grad_accum_reset(self, stream=None):
         _check(self.lib.varuna_stage_grad_accum_reset(self.handle, _stream_ptr(stream)))
+
+    def grad_flush(self, stream=None):
+        _check(self.lib.varuna_stage_grad_flush(self.handle, _stream_ptr(stream)))
 
     # -- hooks --------------------------------------------------------------
     def debug_forward_save(self, mb: int, x: torch.Tensor, y: torch.Tensor, stream=None):

@@ -54,7 +54,7 @@ varuna_status_t fail(varuna_status_t code, const char* fmt, ...) {
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 struct Dims {
-  int L, h, a, d, s, b, M, f, causal, dtype;
+  int L, h, a, d, s, b, M, f, causal, dtype, G;
   float eps;
   int64_t T, E, F;  // tokens, T*h, T*f
   size_t es;        // bytes per activation / parameter element
@@ -74,6 +74,8 @@ varuna_status_t make_dims(const varuna_stage_config_t* c, Dims* o) {
   o->s = c->seq_len; o->b = c->micro_batch; o->M = c->n_micro_batches;
   o->f = c->mlp_hidden ? c->mlp_hidden : 4 * c->hidden;
   o->causal = c->causal; o->dtype = c->dtype;
+  if (c->wgrad_group < 0 || c->wgrad_group > 64) return fail(VARUNA_EINVAL, "wgrad_group must be in [0, 64]");
+  o->G = c->wgrad_group > 1 ? c->wgrad_group : 1;
   o->eps = c->ln_eps > 0.0f ? c->ln_eps : 1e-5f;
   o->T = (int64_t)o->b * o->s; o->E = o->T * o->h; o->F = o->T * o->f;
   o->es = c->dtype == VARUNA_F32 ? 4 : 2;
@@ -96,13 +98,22 @@ ParamOffsets param_offsets(const Dims& D) {
   return p;
 }
 
-// byte offsets inside the workspace
-struct LayerArea { size_t stats1, xn1, qkv, lse, ctx, x1, stats2, xn2, u, g, y, end; };
+// byte offsets inside the workspace.
+// The operands of the weight-gradient GEMMs (xn1, ctx, xn2, g and dy, du, dx1, dqkv of every
+// layer) are rings of G micro-batch slots stacked along the token dimension, so that one
+// GEMM with reduction length cnt*T covers the cnt micro-batches gathered since the last
+// flush (G = 1: plain per-micro-batch accumulation).
+struct LayerArea {
+  size_t stats1, qkv, lse, x1, stats2, u, y;   // one copy
+  size_t xn1, ctx, xn2, g;                     // rings written by the recompute pass
+  size_t dy, du, dx1, dqkv;                    // rings written by the backward pass
+};
 struct Workspace {
-  std::vector<LayerArea> layer;  // saved activations, one area per layer
+  std::vector<LayerArea> layer;  // per layer: saved activations and backward rings
+  LayerArea fwd;                 // scratch of the forward pass (nothing of it is kept)
   size_t saved_begin, saved_end;
   size_t ping[2];                // forward layer outputs (discarded)
-  size_t dping[2], du, dxn, dx1, dctx, dqkv, delta, partial;
+  size_t dxn, dctx, delta, partial;
   size_t total;
 };
 Workspace carve(const Dims& D) {
@@ -111,18 +122,23 @@ Workspace carve(const Dims& D) {
   auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes); return r; };
   const size_t E = (size_t)D.E * D.es, F = (size_t)D.F * D.es;
   const size_t lse = (size_t)D.b * D.a * D.s * sizeof(float), st = (size_t)2 * D.T * sizeof(float);
+  auto area = [&](size_t G, bool with_backward) {
+    LayerArea a{};
+    a.stats1 = take(st); a.xn1 = take(G * E); a.qkv = take(3 * E); a.lse = take(lse); a.ctx = take(G * E);
+    a.x1 = take(E); a.stats2 = take(st); a.xn2 = take(G * E); a.u = take(F); a.g = take(G * F); a.y = take(E);
+    if (with_backward) { a.dy = take(G * E); a.du = take(G * F); a.dx1 = take(G * E); a.dqkv = take(G * 3 * E); }
+    return a;
+  };
   w.saved_begin = o;
-  for (int l = 0; l < D.L; ++l) {
-    LayerArea a;
-    a.stats1 = take(st); a.xn1 = take(E); a.qkv = take(3 * E); a.lse = take(lse); a.ctx = take(E);
-    a.x1 = take(E); a.stats2 = take(st); a.xn2 = take(E); a.u = take(F); a.g = take(F); a.y = take(E);
-    a.end = o;
-    w.layer.push_back(a);
-  }
+  for (int l = 0; l < D.L; ++l) w.layer.push_back(area((size_t)D.G, false));
   w.saved_end = o;
+  for (int l = 0; l < D.L; ++l) {
+    LayerArea& a = w.layer[l];
+    a.dy = take((size_t)D.G * E); a.du = take((size_t)D.G * F); a.dx1 = take((size_t)D.G * E); a.dqkv = take((size_t)D.G * 3 * E);
+  }
+  w.fwd = area(1, false);
   w.ping[0] = take(E); w.ping[1] = take(E);
-  w.dping[0] = take(E); w.dping[1] = take(E);
-  w.du = take(F); w.dxn = take(E); w.dx1 = take(E); w.dctx = take(E); w.dqkv = take(3 * E);
+  w.dxn = take(E); w.dctx = take(E);
   w.delta = take(lse);
   int64_t widest = 3 * (int64_t)D.h;
   if (D.f > widest) widest = D.f;
@@ -144,6 +160,7 @@ struct varuna_stage {
   char* boundary;
   char* work;
   std::vector<char> forwarded;
+  int pending = 0;  // micro-batches whose weight-gradient GEMMs have not been issued yet
   // profiler
   bool prof_on = false;
   std::vector<hipEvent_t> ev;  // pairs
@@ -279,12 +296,14 @@ struct StageOps {
     return D.causal ? dense * 0.5 : dense;
   }
 
-  // One layer forward.  save: also store stats, lse, u.  skip_mlp2: stop after GeLU.
-  hipError_t layer_forward(int l, const T* x, T* y, const LayerArea& A, bool save, bool skip_mlp2) {
+  // One layer forward.  rs: ring slot of the wgrad operands (xn1, ctx, xn2, g).
+  // save: also store stats, lse, u.  skip_mlp2: stop after GeLU.
+  hipError_t layer_forward(int l, const T* x, T* y, const LayerArea& A, int rs, bool save, bool skip_mlp2) {
     hipError_t e;
     const int64_t T_ = D.T;
-    T* xn1 = wsp<T>(A.xn1); T* qkv = wsp<T>(A.qkv); T* ctx = wsp<T>(A.ctx); T* x1 = wsp<T>(A.x1);
-    T* xn2 = wsp<T>(A.xn2); T* u = wsp<T>(A.u); T* g = wsp<T>(A.g);
+    T* xn1 = wsp<T>(A.xn1) + (size_t)rs * D.E; T* qkv = wsp<T>(A.qkv); T* ctx = wsp<T>(A.ctx) + (size_t)rs * D.E;
+    T* x1 = wsp<T>(A.x1); T* xn2 = wsp<T>(A.xn2) + (size_t)rs * D.E; T* u = wsp<T>(A.u);
+    T* g = wsp<T>(A.g) + (size_t)rs * D.F;
     float* stats1 = save ? wsp<float>(A.stats1) : nullptr;
     float* stats2 = save ? wsp<float>(A.stats2) : nullptr;
     float* lse = save ? wsp<float>(A.lse) : nullptr;
@@ -312,48 +331,66 @@ struct StageOps {
     return launch_colsum<T>(a, out, wsp<float>(S->ws.partial), D.T, n, st);
   }
 
-  // One layer backward.  x: the layer's input, dy: gradient of its output, dx: gradient of its input.
-  hipError_t layer_backward(int l, const T* x, const T* dy, T* dx, const LayerArea& A) {
+  // One layer backward for ring slot rs.  x: the layer's input; the gradient of its output
+  // already sits in slot rs of the layer's dy ring; dx: gradient of its input.  The four
+  // weight-gradient GEMMs are not issued here (see flush_wgrads): this pass leaves their
+  // operands in the rings.
+  hipError_t layer_backward(int l, const T* x, T* dx, const LayerArea& A, int rs) {
     hipError_t e;
     const int64_t T_ = D.T;
     const Workspace& W = S->ws;
-    const T* xn1 = wsp<T>(A.xn1); const T* qkv = wsp<T>(A.qkv); const T* ctx = wsp<T>(A.ctx);
-    const T* x1 = wsp<T>(A.x1); const T* xn2 = wsp<T>(A.xn2); const T* u = wsp<T>(A.u); const T* g = wsp<T>(A.g);
+    const T* qkv = wsp<T>(A.qkv); const T* ctx = wsp<T>(A.ctx) + (size_t)rs * D.E;
+    const T* x1 = wsp<T>(A.x1); const T* u = wsp<T>(A.u);
     const float* stats1 = wsp<float>(A.stats1); const float* stats2 = wsp<float>(A.stats2);
     const float* lse = wsp<float>(A.lse);
-    T* du = wsp<T>(W.du); T* dxn = wsp<T>(W.dxn); T* dx1 = wsp<T>(W.dx1); T* dctx = wsp<T>(W.dctx);
-    T* dqkv = wsp<T>(W.dqkv); float* delta = wsp<float>(W.delta); float* partial = wsp<float>(W.partial);
+    const T* dy = wsp<T>(A.dy) + (size_t)rs * D.E;
+    T* du = wsp<T>(A.du) + (size_t)rs * D.F; T* dx1 = wsp<T>(A.dx1) + (size_t)rs * D.E;
+    T* dqkv = wsp<T>(A.dqkv) + (size_t)rs * 3 * D.E;
+    T* dxn = wsp<T>(W.dxn); T* dctx = wsp<T>(W.dctx);
+    float* delta = wsp<float>(W.delta); float* partial = wsp<float>(W.partial);
 
-    // MLP2: du = (dy W2) * GeLU'(u); dW2 += dy^T g; db2 += colsum(dy)
+    // MLP2: du = (dy W2) * GeLU'(u); db2 += colsum(dy)
     if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_DGELU, T_, D.f, D.h, dy, param(l, VARUNA_P_W2), nullptr, u, du, nullptr, nullptr))) return e;
-    if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.h, D.f, T_, dy, g, nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_W2)))) return e;
     if ((e = colsum(dy, grad(l, VARUNA_P_B2), D.h))) return e;
-    // MLP1: dxn2 = du W1; dW1 += du^T xn2; db1 += colsum(du)
+    // MLP1: dxn2 = du W1; db1 += colsum(du)
     if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_PLAIN, T_, D.h, D.f, du, param(l, VARUNA_P_W1), nullptr, nullptr, dxn, nullptr, nullptr))) return e;
-    if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.f, D.h, T_, du, xn2, nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_W1)))) return e;
     if ((e = colsum(du, grad(l, VARUNA_P_B1), D.f))) return e;
     // LN2: dx1 = dy + LN'(dxn2)
     {
       Bracket br(S, st, VARUNA_K_LN_BWD, 0, 6.0 * D.E * sizeof(T));
       if ((e = launch_layernorm_bwd<T>(dxn, x1, stats2, param(l, VARUNA_P_LN2_G), dy, dx1, grad(l, VARUNA_P_LN2_G), grad(l, VARUNA_P_LN2_B), partial, T_, D.h, st))) return e;
     }
-    // proj: dctx = dx1 Wo; dWo += dx1^T ctx; dbo += colsum(dx1)
+    // proj: dctx = dx1 Wo; dbo += colsum(dx1)
     if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_PLAIN, T_, D.h, D.h, dx1, param(l, VARUNA_P_WO), nullptr, nullptr, dctx, nullptr, nullptr))) return e;
-    if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.h, D.h, T_, dx1, ctx, nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_WO)))) return e;
     if ((e = colsum(dx1, grad(l, VARUNA_P_BO), D.h))) return e;
     // attention
     {
       Bracket br(S, st, VARUNA_K_ATTN_BWD, 2.5 * attn_flops_fwd(), 9.0 * D.E * sizeof(T));
       if ((e = AttnDispatch<T>::bwd(0, qkv, ctx, lse, dctx, dqkv, delta, D.b, D.s, D.a, D.d, D.causal, st))) return e;
     }
-    // QKV: dxn1 = dqkv Wqkv; dWqkv += dqkv^T xn1; dbqkv += colsum(dqkv)
+    // QKV: dxn1 = dqkv Wqkv; dbqkv += colsum(dqkv)
     if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_PLAIN, T_, D.h, 3 * D.h, dqkv, param(l, VARUNA_P_WQKV), nullptr, nullptr, dxn, nullptr, nullptr))) return e;
-    if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, 3 * D.h, D.h, T_, dqkv, xn1, nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_WQKV)))) return e;
     if ((e = colsum(dqkv, grad(l, VARUNA_P_BQKV), 3 * D.h))) return e;
     // LN1: dx = dx1 + LN'(dxn1)
     {
       Bracket br(S, st, VARUNA_K_LN_BWD, 0, 6.0 * D.E * sizeof(T));
       if ((e = launch_layernorm_bwd<T>(dxn, x, stats1, param(l, VARUNA_P_LN1_G), dx1, dx, grad(l, VARUNA_P_LN1_G), grad(l, VARUNA_P_LN1_B), partial, T_, D.h, st))) return e;
+    }
+    return hipSuccess;
+  }
+
+  // dW += dY^T X for the four matrices of every layer, over the `cnt` micro-batches whose
+  // operands sit in ring slots 0..cnt-1: the slots are stacked along the token dimension,
+  // so each is ONE GEMM with reduction length cnt*T and one fp32 read-modify-write of dW.
+  hipError_t flush_wgrads(int cnt) {
+    hipError_t e;
+    const int64_t K = (int64_t)cnt * D.T;
+    for (int l = D.L - 1; l >= 0; --l) {
+      const LayerArea& A = S->ws.layer[l];
+      if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.h, D.f, K, wsp<T>(A.dy), wsp<T>(A.g), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_W2)))) return e;
+      if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.f, D.h, K, wsp<T>(A.du), wsp<T>(A.xn2), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_W1)))) return e;
+      if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.h, D.h, K, wsp<T>(A.dx1), wsp<T>(A.ctx), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_WO)))) return e;
+      if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, 3 * D.h, D.h, K, wsp<T>(A.dqkv), wsp<T>(A.xn1), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_WQKV)))) return e;
     }
     return hipSuccess;
   }
@@ -366,28 +403,28 @@ struct StageOps {
     return hipMemcpyAsync(slot(mb), x_in, (size_t)D.E * sizeof(T), hipMemcpyDeviceToDevice, st);
   }
 
-  // Forward that keeps nothing but the boundary slot: every layer reuses area 0.
+  // Forward that keeps nothing but the boundary slot: every layer reuses the forward scratch.
   hipError_t forward(int mb, const T* x_in, T* y_out) {
     hipError_t e;
     if ((e = store_boundary(mb, x_in))) return e;
     const T* x = slot(mb);
     for (int l = 0; l < D.L; ++l) {
       T* y = (l == D.L - 1) ? y_out : wsp<T>(S->ws.ping[l & 1]);
-      if ((e = layer_forward(l, x, y, S->ws.layer[0], false, false))) return e;
+      if ((e = layer_forward(l, x, y, S->ws.fwd, 0, false, false))) return e;
       x = y;
     }
     return hipSuccess;
   }
 
-  // Recompute from the boundary slot into the per-layer areas.  with_output: also
-  // produce the stage output (the debug hook wants it; the backward pass does not).
-  hipError_t recompute(int mb, T* y_out) {
+  // Recompute from the boundary slot into the per-layer areas, ring slot rs.  With y_out
+  // the stage output is produced too (the debug hook wants it; the backward pass does not).
+  hipError_t recompute(int mb, T* y_out, int rs) {
     hipError_t e;
     const T* x = slot(mb);
     for (int l = 0; l < D.L; ++l) {
       const bool last = (l == D.L - 1);
       T* y = last ? y_out : wsp<T>(S->ws.layer[l].y);
-      if ((e = layer_forward(l, x, y, S->ws.layer[l], true, last && y_out == nullptr))) return e;
+      if ((e = layer_forward(l, x, y, S->ws.layer[l], rs, true, last && y_out == nullptr))) return e;
       x = y;
     }
     return hipSuccess;
@@ -395,15 +432,29 @@ struct StageOps {
 
   hipError_t backward(int mb, const T* dy_in, T* dx_out) {
     hipError_t e;
-    if ((e = recompute(mb, nullptr))) return e;
-    const T* dy = dy_in;
+    const int rs = S->pending;
+    if ((e = recompute(mb, nullptr, rs))) return e;
+    {  // the upstream gradient joins the top layer's dy ring
+      Bracket br(S, st, VARUNA_K_OTHER, 0, 2.0 * D.E * sizeof(T));
+      if ((e = hipMemcpyAsync(wsp<T>(S->ws.layer[D.L - 1].dy) + (size_t)rs * D.E, dy_in, (size_t)D.E * sizeof(T), hipMemcpyDeviceToDevice, st))) return e;
+    }
     for (int l = D.L - 1; l >= 0; --l) {
       const T* x = (l == 0) ? slot(mb) : wsp<T>(S->ws.layer[l - 1].y);
-      T* dx = (l == 0) ? dx_out : wsp<T>(S->ws.dping[l & 1]);
-      if ((e = layer_backward(l, x, dy, dx, S->ws.layer[l]))) return e;
-      dy = dx;
+      T* dx = (l == 0) ? dx_out : wsp<T>(S->ws.layer[l - 1].dy) + (size_t)rs * D.E;
+      if ((e = layer_backward(l, x, dx, S->ws.layer[l], rs))) return e;
+    }
+    if (++S->pending == D.G) {
+      if ((e = flush_wgrads(S->pending))) return e;
+      S->pending = 0;
     }
     return hipSuccess;
+  }
+
+  hipError_t flush() {
+    if (S->pending == 0) return hipSuccess;
+    hipError_t e = flush_wgrads(S->pending);
+    S->pending = 0;
+    return e;
   }
 };
 
@@ -507,11 +558,11 @@ varuna_status_t varuna_stage_debug_forward_save(varuna_stage_t* st, int32_t mb, 
   if (st->D.dtype == VARUNA_F32) {
     StageOps<float> ops(st, s);
     e = ops.store_boundary(mb, static_cast<const float*>(x_in));
-    if (e == hipSuccess) e = ops.recompute(mb, static_cast<float*>(y_out));
+    if (e == hipSuccess) e = ops.recompute(mb, static_cast<float*>(y_out), st->pending);
   } else {
     StageOps<bf16> ops(st, s);
     e = ops.store_boundary(mb, static_cast<const bf16*>(x_in));
-    if (e == hipSuccess) e = ops.recompute(mb, static_cast<bf16*>(y_out));
+    if (e == hipSuccess) e = ops.recompute(mb, static_cast<bf16*>(y_out), st->pending);
   }
   if ((rc = hip_result(e, "varuna_stage_debug_forward_save"))) return rc;
   st->forwarded[mb] = 1;
@@ -542,9 +593,17 @@ varuna_status_t varuna_stage_grad_accum_reset(varuna_stage_t* st, void* hip_stre
   if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const size_t n = st->po.per_layer * st->D.L;
+  st->pending = 0;  // operands gathered for a not yet issued weight-gradient group are dropped
   Bracket br(st, s, VARUNA_K_OTHER, 0, 4.0 * n);
   hipLaunchKernelGGL(fill_zero_f32_kernel, dim3(2048), dim3(256), 0, s, st->grads, n);
   return hip_result(hipGetLastError(), "varuna_stage_grad_accum_reset");
+}
+
+varuna_status_t varuna_stage_grad_flush(varuna_stage_t* st, void* hip_stream) {
+  if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = (st->D.dtype == VARUNA_F32) ? StageOps<float>(st, s).flush() : StageOps<bf16>(st, s).flush();
+  return hip_result(e, "varuna_stage_grad_flush");
 }
 
 varuna_status_t varuna_stage_profile_enable(varuna_stage_t* st, int32_t on) {

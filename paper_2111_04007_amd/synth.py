@@ -41,6 +41,7 @@ class StageConfig:
     w_std: float = 0.02
     ln_eps: float = 1e-5
     seed: int = 20211104
+    wgrad_group: int = 1  # micro-batches per weight-gradient GEMM (library knob, not part of the workload)
 
     @property
     def tokens(self) -> int:

@@ -39,6 +39,7 @@ def gpu_stage_step(cfg, params, xs, dys, device="cuda:0", interleave=False):
             st.forward(m, dx_[m], ys[m])
         for m in range(n):
             st.backward_recompute(m, ddy[m], dxs[m])
+    st.grad_flush()   # issues a pending weight-gradient group (no-op when wgrad_group <= 1)
     torch.cuda.synchronize()
     return st, [y.cpu() for y in ys], [d.cpu() for d in dxs]
 

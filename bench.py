@@ -28,6 +28,12 @@ def parse():
     ap.add_argument("--micro-batches", type=int, default=0, help="override M (default: the config's)")
     ap.add_argument("--wgrad-group", type=int, default=4,
                     help="micro-batches per weight-gradient GEMM (library knob; 1 = per micro-batch)")
+    ap.add_argument("--stage", choices=("middle", "last"), default="middle",
+                    help="middle: M forwards then M recompute+backward calls (the headline step); last: the "
+                         "last pipeline stage's step, M times forward_keep + backward_stored, no recompute")
+    ap.add_argument("--calibrate", default="",
+                    help="comma-separated micro-batch sizes m: instead of the step benchmark, print F(m), "
+                         "recompute+backward(m), keeping-forward(m) and stored-backward(m) per m and the m picked")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
     return ap.parse_args()
@@ -84,6 +90,18 @@ def main():
     from paper_2111_04007_amd import CONFIGS, binding as B, flops, synth
 
     cfg = CONFIGS[args.config]
+    if args.calibrate:
+        from paper_2111_04007_amd import calibrate
+        ms = [int(v) for v in args.calibrate.split(",")]
+        torch.cuda.set_device(0)
+        rows = calibrate.sweep(cfg, ms, n_mb=args.micro_batches or 4, reps=max(1, args.steps))
+        pick = calibrate.pick_micro_batch([r["m"] for r in rows], [r["F_per_example_ms"] for r in rows])
+        print(json.dumps({"metric": "calibration: stage compute time per micro-batch size m (ms)", "unit": "ms",
+                          "n_gpus": 1, "dtype": cfg.dtype, "data": "synthetic",
+                          "config": {"workload": cfg.name + " swept over micro_batch", "n_layers": cfg.n_layers,
+                                     "hidden": cfg.hidden, "seq_len": cfg.seq_len},
+                          "rows": rows, "picked_m": pick, "rule": "lowest m whose F(m)/m no larger m beats by > 3 %"}))
+        return
     if args.micro_batches:
         cfg = cfg.replace(n_micro_batches=args.micro_batches)
     cfg = cfg.replace(wgrad_group=max(1, args.wgrad_group))
@@ -98,12 +116,19 @@ def main():
     dxs = torch.empty_like(xs)
     stream = torch.cuda.current_stream()
 
+    last = args.stage == "last"
+
     def step():
         st.grad_accum_reset(stream)
-        for m in range(M):
-            st.forward(m, xs[m], ys[m], stream)
-        for m in range(M):
-            st.backward_recompute(m, dys[m], dxs[m], stream)
+        if last:
+            for m in range(M):
+                st.forward_keep(m, xs[m], ys[m], stream)
+                st.backward_stored(m, dys[m], dxs[m], stream)
+        else:
+            for m in range(M):
+                st.forward(m, xs[m], ys[m], stream)
+            for m in range(M):
+                st.backward_recompute(m, dys[m], dxs[m], stream)
         st.grad_flush(stream)
 
     for _ in range(args.warmup):
@@ -117,26 +142,45 @@ def main():
     ms_step = wall * 1e3 / args.steps
     ms_mb = ms_step / M
 
-    # separate forward / recompute+backward timing with events on the same stream
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    # separate forward / (recompute+)backward timing with events on the same stream
     st.grad_accum_reset(stream)
-    ev[0].record(stream)
-    for m in range(M):
-        st.forward(m, xs[m], ys[m], stream)
-    ev[1].record(stream)
-    for m in range(M):
-        st.backward_recompute(m, dys[m], dxs[m], stream)
-    st.grad_flush(stream)
-    ev[2].record(stream)
-    torch.cuda.synchronize()
-    ms_f = ev[0].elapsed_time(ev[1]) / M
-    ms_rb = ev[1].elapsed_time(ev[2]) / M
+    if last:
+        evs = []
+        for m in range(M):
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record(stream)
+            st.forward_keep(m, xs[m], ys[m], stream)
+            e[1].record(stream)
+            st.backward_stored(m, dys[m], dxs[m], stream)
+            e[2].record(stream)
+            evs.append(e)
+        st.grad_flush(stream)
+        torch.cuda.synchronize()
+        ms_f = sum(e[0].elapsed_time(e[1]) for e in evs) / M
+        ms_rb = sum(e[1].elapsed_time(e[2]) for e in evs) / M
+    else:
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record(stream)
+        for m in range(M):
+            st.forward(m, xs[m], ys[m], stream)
+        ev[1].record(stream)
+        for m in range(M):
+            st.backward_recompute(m, dys[m], dxs[m], stream)
+        st.grad_flush(stream)
+        ev[2].record(stream)
+        torch.cuda.synchronize()
+        ms_f = ev[0].elapsed_time(ev[1]) / M
+        ms_rb = ev[1].elapsed_time(ev[2]) / M
 
-    # FLOP accounting: 4 forward units per micro-batch (causal-aware), minus the last
-    # layer's MLP2 GEMM that the recompute pass does not need and does not run.
-    skipped = 2.0 * cfg.tokens * cfg.hidden * cfg.mlp_hidden
-    hw_flops_mb = flops.step_flops_per_microbatch(cfg) - skipped
+    # FLOP accounting.  Middle stage: 4 forward units per micro-batch (causal-aware), minus the
+    # last layer's MLP2 GEMM that the recompute pass does not need and does not run.  Last stage:
+    # 3 forward units (no recompute).
     useful_flops_mb = flops.useful_flops_per_microbatch(cfg)
+    if last:
+        hw_flops_mb = useful_flops_mb
+    else:
+        skipped = 2.0 * cfg.tokens * cfg.hidden * cfg.mlp_hidden
+        hw_flops_mb = flops.step_flops_per_microbatch(cfg) - skipped
     tflops = hw_flops_mb * M / (ms_step * 1e-3) / 1e12
     frac_peak = tflops * 1e12 / flops.MI355X_BF16_DENSE_PEAK
 
@@ -148,10 +192,16 @@ def main():
         for _ in range(args.steps):
             st.grad_accum_reset(stream)
             for m in range(M):
-                st.forward(m, xs[m], ys[m], stream)
-                if m % 8 == 7 or m == M - 1:
+                if last:
+                    st.forward_keep(m, xs[m], ys[m], stream)
+                else:
+                    st.forward(m, xs[m], ys[m], stream)
+                if last or m % 8 == 7 or m == M - 1:
                     _acc(tot, st.profile_collect())
-            for m in range(M):
+                if last:
+                    st.backward_stored(m, dys[m], dxs[m], stream)
+                    _acc(tot, st.profile_collect())
+            for m in range(M if not last else 0):
                 st.backward_recompute(m, dys[m], dxs[m], stream)
                 _acc(tot, st.profile_collect())
             st.grad_flush(stream)
@@ -187,16 +237,17 @@ def main():
     cpu = None if args.no_cpu_baseline else cpu_baseline(cfg)
 
     out = {
-        "metric": "stage fwd+recompute+bwd TFLOP/s (ms/micro-batch and % of bf16 MFMA peak in config)",
+        "metric": ("stage fwd+bwd TFLOP/s, last stage without recompute" if last else
+                   "stage fwd+recompute+bwd TFLOP/s") + " (ms/micro-batch and % of bf16 MFMA peak in config)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {
-            "workload": cfg.name, "n_layers": cfg.n_layers, "hidden": cfg.hidden, "n_heads": cfg.n_heads,
+            "workload": cfg.name + (" (last-stage variant: no recompute)" if last else ""), "n_layers": cfg.n_layers, "hidden": cfg.hidden, "n_heads": cfg.n_heads,
             "seq_len": cfg.seq_len, "micro_batch": cfg.micro_batch, "n_micro_batches": M,
             "mlp_hidden": cfg.mlp_hidden, "causal": cfg.causal, "wgrad_group": cfg.wgrad_group,
             "ms_per_micro_batch": ms_mb, "ms_forward_per_micro_batch": ms_f,
-            "ms_recompute_backward_per_micro_batch": ms_rb,
+            ("ms_backward_per_micro_batch" if last else "ms_recompute_backward_per_micro_batch"): ms_rb,
             "frac_of_bf16_mfma_peak": frac_peak, "peak_tflops_used": flops.MI355X_BF16_DENSE_PEAK / 1e12,
             "useful_tflops_paper_convention": useful_flops_mb * M / (ms_step * 1e-3) / 1e12,
             "flops_per_micro_batch_executed": hw_flops_mb,

@@ -121,6 +121,24 @@ varuna_status_t varuna_stage_backward_recompute(varuna_stage_t* st, int32_t mb,
                                                 const void* dy_in /*device*/,
                                                 void* dx_out /*device*/, void* hip_stream);
 
+/* Last-stage variant (Design Overview, "Tuning pipeline efficiency": in the paper's schedule
+ * the last pipeline stage runs the backward of a micro-batch straight after its forward and
+ * therefore never recomputes).  varuna_stage_forward_keep is varuna_stage_forward that also
+ * leaves every layer's internal activations of micro-batch mb in the workspace, in exactly
+ * the form the recompute pass would leave them (same kernels, same launch geometry);
+ * varuna_stage_backward_stored then runs the backward pass of backward_recompute on them
+ * without recomputing.  The workspace holds the internals of ONE micro-batch: the pair must
+ * be adjacent for a given mb -- any other forward_keep, backward_recompute or
+ * grad_accum_reset in between invalidates them (plain varuna_stage_forward calls of other
+ * slots do not) and backward_stored then returns VARUNA_ESTATE.  Arguments, layouts, the
+ * accumulation into grads_f32 and the wgrad_group deferral are those of the two calls above;
+ * outputs and gradients are bit-identical to the forward / backward_recompute pair. */
+varuna_status_t varuna_stage_forward_keep(varuna_stage_t* st, int32_t mb, const void* x_in /*device*/,
+                                          void* y_out /*device*/, void* hip_stream);
+varuna_status_t varuna_stage_backward_stored(varuna_stage_t* st, int32_t mb,
+                                             const void* dy_in /*device*/,
+                                             void* dx_out /*device*/, void* hip_stream);
+
 /* With wgrad_group G > 1 the operands of the weight-gradient products dW += dY^T X are kept
  * for up to G micro-batches (the workspace holds G slots of them, stacked along the token
  * dimension) and each dW receives ONE GEMM over G*T tokens and one fp32 read-modify-write:

@@ -27,6 +27,7 @@ OP_FWD, OP_DGRAD, OP_WGRAD = 0, 1, 2
 EXPORTS = (
     "varuna_stage_query_sizes", "varuna_stage_param_offset", "varuna_stage_create",
     "varuna_stage_forward", "varuna_stage_backward_recompute", "varuna_stage_grad_accum_reset",
+    "varuna_stage_forward_keep", "varuna_stage_backward_stored",
     "varuna_stage_grad_flush", "varuna_stage_destroy", "varuna_last_error", "varuna_stage_debug_forward_save",
     "varuna_stage_debug_saved_region", "varuna_stage_profile_enable", "varuna_stage_profile_collect",
     "varuna_op_gemm", "varuna_op_layernorm_fwd", "varuna_op_layernorm_bwd", "varuna_op_colsum",
@@ -74,6 +75,8 @@ def load():
         "varuna_stage_create": (i32, [pcfg, vp, vp, vp, vp, C.POINTER(vp)]),
         "varuna_stage_forward": (i32, [vp, i32, vp, vp, vp]),
         "varuna_stage_backward_recompute": (i32, [vp, i32, vp, vp, vp]),
+        "varuna_stage_forward_keep": (i32, [vp, i32, vp, vp, vp]),
+        "varuna_stage_backward_stored": (i32, [vp, i32, vp, vp, vp]),
         "varuna_stage_grad_accum_reset": (i32, [vp, vp]),
         "varuna_stage_grad_flush": (i32, [vp, vp]),
         "varuna_stage_destroy": (i32, [vp]),
@@ -182,6 +185,12 @@ class Stage:
 
     def backward_recompute(self, mb: int, dy: torch.Tensor, dx: torch.Tensor, stream=None):
         _check(self.lib.varuna_stage_backward_recompute(self.handle, mb, _ptr(dy), _ptr(dx), _stream_ptr(stream)))
+
+    def forward_keep(self, mb: int, x: torch.Tensor, y: torch.Tensor, stream=None):
+        _check(self.lib.varuna_stage_forward_keep(self.handle, mb, _ptr(x), _ptr(y), _stream_ptr(stream)))
+
+    def backward_stored(self, mb: int, dy: torch.Tensor, dx: torch.Tensor, stream=None):
+        _check(self.lib.varuna_stage_backward_stored(self.handle, mb, _ptr(dy), _ptr(dx), _stream_ptr(stream)))
 
     def grad_accum_reset(self, stream=None):
         _check(self.lib.varuna_stage_grad_accum_reset(self.handle, _stream_ptr(stream)))

@@ -161,6 +161,8 @@ struct varuna_stage {
   char* work;
   std::vector<char> forwarded;
   int pending = 0;  // micro-batches whose weight-gradient GEMMs have not been issued yet
+  int kept_mb = -1;  // micro-batch whose internals forward_keep left in the layer areas (-1: none)
+  int kept_slot = 0; // ring slot they were written to
   // profiler
   bool prof_on = false;
   std::vector<hipEvent_t> ev;  // pairs
@@ -430,10 +432,12 @@ struct StageOps {
     return hipSuccess;
   }
 
-  hipError_t backward(int mb, const T* dy_in, T* dx_out) {
+  // Backward of micro-batch mb into ring slot `pending`; with recompute_first the internals
+  // are first re-derived from the boundary slot, otherwise they must already sit there.
+  hipError_t backward(int mb, const T* dy_in, T* dx_out, bool recompute_first) {
     hipError_t e;
     const int rs = S->pending;
-    if ((e = recompute(mb, nullptr, rs))) return e;
+    if (recompute_first && (e = recompute(mb, nullptr, rs))) return e;
     {  // the upstream gradient joins the top layer's dy ring
       Bracket br(S, st, VARUNA_K_OTHER, 0, 2.0 * D.E * sizeof(T));
       if ((e = hipMemcpyAsync(wsp<T>(S->ws.layer[D.L - 1].dy) + (size_t)rs * D.E, dy_in, (size_t)D.E * sizeof(T), hipMemcpyDeviceToDevice, st))) return e;
@@ -469,6 +473,27 @@ varuna_status_t hip_result(hipError_t e, const char* what) {
   if (e == hipSuccess) return VARUNA_OK;
   if (e == hipErrorInvalidConfiguration) return fail(VARUNA_EUNSUPPORTED, "%s: kernel configuration does not support this shape", what);
   return fail(VARUNA_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Forward through the per-layer areas (the recompute pass with the stage output produced).
+varuna_status_t keep_forward(varuna_stage_t* st, int32_t mb, const void* x_in, void* y_out, void* hip_stream, const char* what) {
+  varuna_status_t rc = check_call(st, mb, x_in, y_out);
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  st->kept_mb = -1;
+  if (st->D.dtype == VARUNA_F32) {
+    StageOps<float> ops(st, s);
+    e = ops.store_boundary(mb, static_cast<const float*>(x_in));
+    if (e == hipSuccess) e = ops.recompute(mb, static_cast<float*>(y_out), st->pending);
+  } else {
+    StageOps<bf16> ops(st, s);
+    e = ops.store_boundary(mb, static_cast<const bf16*>(x_in));
+    if (e == hipSuccess) e = ops.recompute(mb, static_cast<bf16*>(y_out), st->pending);
+  }
+  if ((rc = hip_result(e, what))) return rc;
+  st->forwarded[mb] = 1;
+  return VARUNA_OK;
 }
 
 }  // namespace
@@ -551,22 +576,7 @@ varuna_status_t varuna_stage_forward(varuna_stage_t* st, int32_t mb, const void*
 }
 
 varuna_status_t varuna_stage_debug_forward_save(varuna_stage_t* st, int32_t mb, const void* x_in, void* y_out, void* hip_stream) {
-  varuna_status_t rc = check_call(st, mb, x_in, y_out);
-  if (rc) return rc;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  hipError_t e;
-  if (st->D.dtype == VARUNA_F32) {
-    StageOps<float> ops(st, s);
-    e = ops.store_boundary(mb, static_cast<const float*>(x_in));
-    if (e == hipSuccess) e = ops.recompute(mb, static_cast<float*>(y_out), st->pending);
-  } else {
-    StageOps<bf16> ops(st, s);
-    e = ops.store_boundary(mb, static_cast<const bf16*>(x_in));
-    if (e == hipSuccess) e = ops.recompute(mb, static_cast<bf16*>(y_out), st->pending);
-  }
-  if ((rc = hip_result(e, "varuna_stage_debug_forward_save"))) return rc;
-  st->forwarded[mb] = 1;
-  return VARUNA_OK;
+  return keep_forward(st, mb, x_in, y_out, hip_stream, "varuna_stage_debug_forward_save");
 }
 
 varuna_status_t varuna_stage_debug_saved_region(const varuna_stage_t* st, size_t* offset_bytes, size_t* n_bytes) {
@@ -582,9 +592,34 @@ varuna_status_t varuna_stage_backward_recompute(varuna_stage_t* st, int32_t mb, 
   if (!st->forwarded[mb]) return fail(VARUNA_ESTATE, "backward_recompute(%d) without a forward of that slot", mb);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipError_t e = (st->D.dtype == VARUNA_F32)
-                     ? StageOps<float>(st, s).backward(mb, static_cast<const float*>(dy_in), static_cast<float*>(dx_out))
-                     : StageOps<bf16>(st, s).backward(mb, static_cast<const bf16*>(dy_in), static_cast<bf16*>(dx_out));
+                     ? StageOps<float>(st, s).backward(mb, static_cast<const float*>(dy_in), static_cast<float*>(dx_out), true)
+                     : StageOps<bf16>(st, s).backward(mb, static_cast<const bf16*>(dy_in), static_cast<bf16*>(dx_out), true);
+  st->kept_mb = -1;  // the recompute pass overwrote the layer areas
   if ((rc = hip_result(e, "varuna_stage_backward_recompute"))) return rc;
+  st->forwarded[mb] = 0;
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_stage_forward_keep(varuna_stage_t* st, int32_t mb, const void* x_in, void* y_out, void* hip_stream) {
+  varuna_status_t rc = keep_forward(st, mb, x_in, y_out, hip_stream, "varuna_stage_forward_keep");
+  if (rc) return rc;
+  st->kept_mb = mb;
+  st->kept_slot = st->pending;
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_stage_backward_stored(varuna_stage_t* st, int32_t mb, const void* dy_in, void* dx_out, void* hip_stream) {
+  varuna_status_t rc = check_call(st, mb, dy_in, dx_out);
+  if (rc) return rc;
+  if (st->kept_mb != mb || st->kept_slot != st->pending || !st->forwarded[mb])
+    return fail(VARUNA_ESTATE, "backward_stored(%d): the workspace does not hold that micro-batch's activations "
+                "(needs varuna_stage_forward_keep(%d) directly before)", mb, mb);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = (st->D.dtype == VARUNA_F32)
+                     ? StageOps<float>(st, s).backward(mb, static_cast<const float*>(dy_in), static_cast<float*>(dx_out), false)
+                     : StageOps<bf16>(st, s).backward(mb, static_cast<const bf16*>(dy_in), static_cast<bf16*>(dx_out), false);
+  st->kept_mb = -1;
+  if ((rc = hip_result(e, "varuna_stage_backward_stored"))) return rc;
   st->forwarded[mb] = 0;
   return VARUNA_OK;
 }
@@ -594,6 +629,7 @@ varuna_status_t varuna_stage_grad_accum_reset(varuna_stage_t* st, void* hip_stre
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const size_t n = st->po.per_layer * st->D.L;
   st->pending = 0;  // operands gathered for a not yet issued weight-gradient group are dropped
+  st->kept_mb = -1;
   Bracket br(st, s, VARUNA_K_OTHER, 0, 4.0 * n);
   hipLaunchKernelGGL(fill_zero_f32_kernel, dim3(2048), dim3(256), 0, s, st->grads, n);
   return hip_result(hipGetLastError(), "varuna_stage_grad_accum_reset");

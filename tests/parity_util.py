@@ -16,9 +16,10 @@ def oracle_shape(cfg: synth.StageConfig) -> O.StageShape:
                         cfg.mlp_hidden, cfg.causal, cfg.ln_eps)
 
 
-def gpu_stage_step(cfg, params, xs, dys, device="cuda:0", interleave=False):
-    """Runs reset, M forwards, M backward_recomputes. Returns (stage, ys, dxs) with
-    outputs as CPU tensors; the accumulated gradients stay in stage.grads."""
+def gpu_stage_step(cfg, params, xs, dys, device="cuda:0", interleave=False, last_stage=False):
+    """Runs reset, M forwards, M backward_recomputes (last_stage: M times forward_keep
+    followed at once by backward_stored). Returns (stage, ys, dxs) with outputs as CPU
+    tensors; the accumulated gradients stay in stage.grads."""
     st = B.Stage(cfg, device)
     st.set_params(params)
     st.grad_accum_reset()
@@ -27,7 +28,11 @@ def gpu_stage_step(cfg, params, xs, dys, device="cuda:0", interleave=False):
     ddy = [d.to(device) for d in dys]
     ys = [torch.empty_like(dx_[0]) for _ in range(n)]
     dxs = [torch.empty_like(dx_[0]) for _ in range(n)]
-    if interleave:
+    if last_stage:
+        for m in range(n):
+            st.forward_keep(m, dx_[m], ys[m])
+            st.backward_stored(m, ddy[m], dxs[m])
+    elif interleave:
         # a legal pipeline order: forward of m+1 issued between backward calls
         st.forward(0, dx_[0], ys[0])
         for m in range(n):

@@ -120,3 +120,18 @@ def test_flop_model_reproduces_paper_throughput_pairs():
     T, h, s = cfg.tokens, cfg.hidden, cfg.seq_len
     assert dense == cfg.n_layers * (24.0 * T * h * h + 4.0 * T * s * h)
     assert abs(3 * dense / cfg.micro_batch - flops.model_flops_per_example(cfg.n_layers, h, s)) < 1e-3 * dense
+
+
+def test_pick_micro_batch_rule():
+    """Parametrized Simulation: the lowest m at which F(m)/m stops improving.  The paper's own
+    datum (Job Morphing, "Problem setting and constraints": m=8 is 26 % better per example
+    than m=4 for BERT-large) must move the pick past m=4."""
+    from paper_2111_04007_amd.calibrate import pick_micro_batch
+    ms = [1, 2, 4, 8, 16]
+    assert pick_micro_batch(ms, [10.0, 7.0, 5.0, 5.0 / 1.26, 5.0 / 1.26 * 0.99]) == 8
+    assert pick_micro_batch(ms, [3.0, 3.0, 3.0, 3.0, 3.0]) == 1            # flat: smallest m
+    assert pick_micro_batch(ms, [5.0, 4.0, 3.0, 2.0, 1.0]) == 16           # still improving: largest
+    assert pick_micro_batch([4, 1, 2], [1.0, 2.0, 1.02]) == 2              # order-free; 2 % is within the threshold
+    assert pick_micro_batch(ms, [4.0, 3.0, 3.2, 2.5, 2.49]) == 8           # a non-monotone bump does not stop the search
+    with pytest.raises(ValueError):
+        pick_micro_batch([], [])

@@ -1,5 +1,5 @@
 // bf16 MFMA GEMM for gfx950, second generation: operands go from global memory
-// straight into LDS (global_load_lds_dwordx4, no register staging) into two
+// straight into LDS (buffer_load_dwordx4 ... lds, no register staging) into two
 // stages of 64 k, and MFMA fragments are software-pipelined in registers across
 // k-steps and across k-tiles, with one workgroup barrier per k-tile.
 //
@@ -46,54 +46,94 @@ struct DgLoader {
   static constexpr int NINS = ROWS * DG_BK * 2 / 1024;  // wave-level 1 KB loads per tile
   static constexpr int LPT = NINS / NW;                  // per wave
   static_assert(NINS % NW == 0 && LPT >= 1, "tile rows / waves mismatch");
-  const bf16* gp[LPT];  // per-lane source of each of this wave's loads (k-tile 0)
-  int64_t step;         // elements to advance per k-tile
+  const bf16* base;             // the whole operand is one buffer; loads beyond its extent return zero
+  uint32_t extent;
+  uint32_t voff[LPT];           // per-lane byte offset of each of this wave's loads (k-tile 0)
+  uint32_t step;                // bytes to advance per k-tile
 
-  __device__ __forceinline__ void init(const bf16* g, int64_t ld, int64_t row0, int wave, int lane) {
+  __device__ __forceinline__ void init(const bf16* g, int64_t ld, int64_t row0, int wave, int lane, uint32_t extent_bytes) {
+    base = g;
+    extent = extent_bytes;
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int q = wave + i * NW;
       if (KMAJOR) {
         const int row = q * 8 + (lane >> 3), p = lane & 7;
         const int c = p ^ ((row ^ (row >> 3)) & 7);
-        gp[i] = g + (row0 + row) * ld + c * 8;
+        voff[i] = (uint32_t)(((row0 + row) * ld + c * 8) * 2);
       } else {
         constexpr int CPR = ROWS / 8;  // chunks per k-row
         const int slot = q * 64 + lane, krow = slot / CPR, p = slot % CPR;
         const int c = p ^ ((krow & 3) << 1);
-        gp[i] = g + (int64_t)krow * ld + row0 + c * 8;
+        voff[i] = (uint32_t)(((int64_t)krow * ld + row0 + c * 8) * 2);
       }
     }
-    step = KMAJOR ? (int64_t)DG_BK : (int64_t)DG_BK * ld;
+    step = (uint32_t)((KMAJOR ? (int64_t)DG_BK : (int64_t)DG_BK * ld) * 2);
   }
 
   __device__ __forceinline__ void issue(bf16* lds_tile, int kt, int wave) const {
+#if defined(__HIP_DEVICE_COMPILE__)  // the buffer builtins exist in the device pass only
+    const uint32_t soff = (uint32_t)kt * step;
+    const auto rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(base), 0, extent, 0x00020000);
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int q = wave + i * NW;
-      __builtin_amdgcn_global_load_lds((glb_ptr_t)(gp[i] + kt * step), (lds_ptr_t)(lds_tile + q * 512), 16, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(lds_tile + q * 512), 16, voff[i], soff, 0, 0);
     }
+#endif
   }
 };
 
+// One MFMA operand fragment in registers.  In a kernel whose operands are both k-major the
+// fragments are plain 16-byte LDS loads that the compiler tracks and schedules (HAND = false).
+// A kernel with an m/n-major operand issues ALL its fragment reads as inline assembly
+// (HAND = true): the compiler treats the transposing-read builtin as a possible alias of the
+// direct-to-LDS loads and puts a wait for all of them (vmcnt(0)) in front of the first such
+// read after every issue of the next k-tile, which exposes the full memory latency once per
+// k-tile.  Reads it does not see cost no such wait; their completion is waited for by hand
+// (settle() before the first use), and issue order is source order.
+template <bool KMAJOR, bool HAND> struct DgFragReg;
+template <> struct DgFragReg<true, false> { bf16x8 v; };
+template <> struct DgFragReg<true, true> { bf16x8 v; };
+template <> struct DgFragReg<false, true> { shortx4 lo, hi; };
+
+template <bool HAND> __device__ __forceinline__ bf16x8 dg_value(const DgFragReg<true, HAND>& f) { return f.v; }
+__device__ __forceinline__ bf16x8 dg_value(const DgFragReg<false, true>& f) {
+  union { struct { shortx4 a, b; } s; bf16x8 v; } u;
+  u.s.a = f.lo; u.s.b = f.hi;
+  return u.v;
+}
+// Waits until every LDS read this wave has issued so far has returned; tied to the fragment's
+// registers so that no use of them can be scheduled above it.
+__device__ __forceinline__ void dg_settle(DgFragReg<true, false>&) {}
+__device__ __forceinline__ void dg_settle(DgFragReg<true, true>& f) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.v)); }
+__device__ __forceinline__ void dg_settle(DgFragReg<false, true>& f) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.lo), "+v"(f.hi));
+}
+
 // Fragment reader: the 8 consecutive k-values ks*16 + (lane/32)*8 .. of tile row row_base + lane%32.
-template <int ROWS, bool KMAJOR>
+template <int ROWS, bool KMAJOR, bool HAND>
 struct DgFrag {
-  static __device__ __forceinline__ bf16x8 read(const bf16* lds_tile, int row_base, int ks, int lane) {
-    if (KMAJOR) {
+  static __device__ __forceinline__ void fetch(DgFragReg<KMAJOR, HAND>& f, const bf16* lds_tile, int row_base, int ks, int lane) {
+    if constexpr (KMAJOR) {
       const int row = row_base + (lane & 31), c = ks * 2 + (lane >> 5);
-      return *reinterpret_cast<const bf16x8*>(lds_tile + row * DG_BK + ((c ^ ((row ^ (row >> 3)) & 7)) << 3));
+      const bf16* p0 = lds_tile + row * DG_BK + ((c ^ ((row ^ (row >> 3)) & 7)) << 3);
+      if constexpr (HAND) {
+        const uint32_t a0 = (uint32_t)(uintptr_t)(lds_ptr_t)const_cast<bf16*>(p0);
+        asm volatile("ds_read_b128 %0, %1" : "=v"(f.v) : "v"(a0));
+      } else {
+        f.v = *reinterpret_cast<const bf16x8*>(p0);
+      }
     } else {
       const int blk = lane >> 4, j = lane & 15;
       const int m = row_base + (blk & 1) * 16 + 4 * (j & 3);
       const int kq = j >> 2;  // k-row within its group of 4 == (krow & 3)
       const int c = m >> 3, phys = c ^ (kq << 1);
       const bf16* p0 = lds_tile + (ks * 16 + (blk >> 1) * 8 + kq) * ROWS + phys * 8 + (m & 7);
-      shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)p0);
-      shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)(p0 + 4 * ROWS));
-      union { struct { shortx4 a, b; } s; bf16x8 v; } u;
-      u.s.a = lo; u.s.b = hi;
-      return u.v;
+      const uint32_t a0 = (uint32_t)(uintptr_t)(lds_ptr_t)const_cast<bf16*>(p0);
+      const uint32_t a1 = a0 + 4 * ROWS * 2;
+      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.lo) : "v"(a0));
+      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.hi) : "v"(a1));
     }
   }
 };
@@ -142,11 +182,18 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
   const int tile_n = (logical % width) / gsize;
   const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
 
-  DgLoader<BM, NW, A_KMAJOR> la;
-  DgLoader<BN, NW, B_KMAJOR> lb;
-  la.init(a, lda, m0, wave, lane);
-  lb.init(b, ldb, n0, wave, lane);
-  constexpr int LPT = DgLoader<BM, NW, A_KMAJOR>::LPT + DgLoader<BN, NW, B_KMAJOR>::LPT;
+  // With two waves per SIMD only the upper half of the waves (one per SIMD) issues the
+  // direct loads: a load instruction holds its wave at issue until the texture addresser
+  // takes it (about 16 cycles per 1 KB, 64 per k-tile and CU), and while one wave of a SIMD
+  // is held there the other keeps the matrix pipe fed.
+  constexpr int NI = (NW == 8) ? 4 : NW;
+  const bool issuer = wave >= NW - NI;
+  const int iw = issuer ? wave - (NW - NI) : 0;
+  DgLoader<BM, NI, A_KMAJOR> la;
+  DgLoader<BN, NI, B_KMAJOR> lb;
+  la.init(a, lda, m0, iw, lane, (uint32_t)((A_KMAJOR ? (int64_t)tiles_m * BM : (int64_t)K) * lda * 2));
+  lb.init(b, ldb, n0, iw, lane, (uint32_t)((B_KMAJOR ? (int64_t)tiles_n * BN : (int64_t)K) * ldb * 2));
+  constexpr int LPT = DgLoader<BM, NI, A_KMAJOR>::LPT + DgLoader<BN, NI, B_KMAJOR>::LPT;
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -157,22 +204,26 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int nk = K / DG_BK;
-  la.issue(smem, 0, wave);
-  lb.issue(smem + BM * DG_BK, 0, wave);
-  if (nk > 1) {
-    la.issue(smem + STAGE_ELEMS, 1, wave);
-    lb.issue(smem + STAGE_ELEMS + BM * DG_BK, 1, wave);
-    __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LPT));  // tile 0 landed, tile 1 may be in flight
-  } else {
-    __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(0));
+  if (issuer) {
+    la.issue(smem, 0, iw);
+    lb.issue(smem + BM * DG_BK, 0, iw);
+    if (nk > 1) {
+      la.issue(smem + STAGE_ELEMS, 1, iw);
+      lb.issue(smem + STAGE_ELEMS + BM * DG_BK, 1, iw);
+      __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LPT));  // tile 0 landed, tile 1 may be in flight
+    } else {
+      __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(0));
+    }
   }
   __builtin_amdgcn_s_barrier();
 
-  bf16x8 fa[2][TM], fb[2][TN];
+  constexpr bool HAND = !(A_KMAJOR && B_KMAJOR);
+  DgFragReg<A_KMAJOR, HAND> fa[2][TM];
+  DgFragReg<B_KMAJOR, HAND> fb[2][TN];
 #pragma unroll
-  for (int j = 0; j < TN; ++j) fb[0][j] = DgFrag<BN, B_KMAJOR>::read(smem + BM * DG_BK, wn * WN + j * 32, 0, lane);
+  for (int j = 0; j < TN; ++j) DgFrag<BN, B_KMAJOR, HAND>::fetch(fb[0][j], smem + BM * DG_BK, wn * WN + j * 32, 0, lane);
 #pragma unroll
-  for (int i = 0; i < TM; ++i) fa[0][i] = DgFrag<BM, A_KMAJOR>::read(smem, wm * WM + i * 32, 0, lane);
+  for (int i = 0; i < TM; ++i) DgFrag<BM, A_KMAJOR, HAND>::fetch(fa[0][i], smem, wm * WM + i * 32, 0, lane);
 
   constexpr int NMFMA = TM * TN;
   constexpr int NREAD = (A_KMAJOR ? TM : 2 * TM) + (B_KMAJOR ? TN : 2 * TN);
@@ -183,16 +234,24 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
   auto kstep = [&](auto cur_tag, const bf16* ta, int ks_next) {
     constexpr int cur = decltype(cur_tag)::value;
     const bf16* tb = ta + BM * DG_BK;
+    // hand-waited fragments of set `cur` (fetched during the previous k-step) first, so the
+    // wait does not cover the reads issued next
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[cur ^ 1][j] = DgFrag<BN, B_KMAJOR>::read(tb, wn * WN + j * 32, ks_next, lane);
+    for (int j = 0; j < TN; ++j) dg_settle(fb[cur][j]);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[cur ^ 1][i] = DgFrag<BM, A_KMAJOR>::read(ta, wm * WM + i * 32, ks_next, lane);
+    for (int i = 0; i < TM; ++i) dg_settle(fa[cur][i]);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) DgFrag<BN, B_KMAJOR, HAND>::fetch(fb[cur ^ 1][j], tb, wn * WN + j * 32, ks_next, lane);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) DgFrag<BM, A_KMAJOR, HAND>::fetch(fa[cur ^ 1][i], ta, wm * WM + i * 32, ks_next, lane);
+    // hand-issued reads go out before this k-step's products, so they have the whole k-step to land
+    if constexpr (HAND) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
-    DgInterleave<0, NMFMA, NREAD, RPM, 0>::hint();
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dg_value(fb[cur][j]), dg_value(fa[cur][i]), acc[i][j], 0, 0, 0);
+    if constexpr (!HAND) DgInterleave<0, NMFMA, NREAD, RPM, 0>::hint();
   };
   using S0 = std::integral_constant<int, 0>;
   using S1 = std::integral_constant<int, 1>;
@@ -212,9 +271,9 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
     kstep(S0{}, cur, 3);
     __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
     __builtin_amdgcn_s_barrier();
-    if (kt + 2 < nk) {
-      la.issue(cur, kt + 2, wave);
-      lb.issue(cur + BM * DG_BK, kt + 2, wave);
+    if (issuer && kt + 2 < nk) {
+      la.issue(cur, kt + 2, iw);
+      lb.issue(cur + BM * DG_BK, kt + 2, iw);
     }
     kstep(S1{}, nxt, 0);
   }
@@ -323,8 +382,10 @@ inline bool dg_variant_tile(int variant, MgTile* t) {
 inline bool dg_shape_ok(int variant, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb) {
   MgTile t;
   if (!dg_variant_tile(variant, &t)) return false;
+  // operands are addressed with 32-bit byte offsets from their base (buffer loads)
+  const int64_t a_bytes = (M > K ? M : K) * lda * 2, b_bytes = (N > K ? N : K) * ldb * 2;
   return M % t.bm == 0 && N % t.bn == 0 && K % DG_BK == 0 && K >= DG_BK && lda % 8 == 0 && ldb % 8 == 0 &&
-         (M / t.bm) * (N / t.bn) < (1ll << 31);
+         (M / t.bm) * (N / t.bn) < (1ll << 31) && a_bytes < (1ll << 32) && b_bytes < (1ll << 32);
 }
 
 // Picks between the 256x256 (one workgroup per CU) and 128x128 (two per CU) tiles by the

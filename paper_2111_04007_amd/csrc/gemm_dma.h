@@ -252,6 +252,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
       for (int j = 0; j < TN; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dg_value(fb[cur][j]), dg_value(fa[cur][i]), acc[i][j], 0, 0, 0);
     if constexpr (!HAND) DgInterleave<0, NMFMA, NREAD, RPM, 0>::hint();
+    else __builtin_amdgcn_sched_barrier(0);  // the products stay above the next k-step's wait
   };
   using S0 = std::integral_constant<int, 0>;
   using S1 = std::integral_constant<int, 1>;

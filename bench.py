@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--calibrate", default="",
                     help="comma-separated micro-batch sizes m: instead of the step benchmark, print F(m), "
                          "recompute+backward(m), keeping-forward(m) and stored-backward(m) per m and the m picked")
+    ap.add_argument("--tail", action="store_true",
+                    help="instead of the step benchmark, time the mini-batch tail (gradient statistics + Adam "
+                         "step over the stage's parameters) and print its HBM roofline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
     return ap.parse_args()
@@ -101,6 +104,9 @@ def main():
                           "config": {"workload": cfg.name + " swept over micro_batch", "n_layers": cfg.n_layers,
                                      "hidden": cfg.hidden, "seq_len": cfg.seq_len},
                           "rows": rows, "picked_m": pick, "rule": "lowest m whose F(m)/m no larger m beats by > 3 %"}))
+        return
+    if args.tail:
+        print(json.dumps(bench_tail(cfg, args)))
         return
     if args.micro_batches:
         cfg = cfg.replace(n_micro_batches=args.micro_batches)
@@ -259,6 +265,51 @@ def main():
     }
     st.close()
     print(json.dumps(out))
+
+
+def bench_tail(cfg, args):
+    """Gradient statistics + Adam step over all parameters of the stage, timed with events."""
+    import torch
+    from paper_2111_04007_amd import binding as B, flops, synth
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = cfg.replace(n_micro_batches=1, wgrad_group=1)
+    params, _, _ = synth.device_random_stage(cfg, dev, 1)
+    st = B.Stage(cfg, dev, params_flat=params)
+    n = st.grads.numel()
+    st.grads.normal_(0.0, 1.0)
+    master = st.params.to(torch.float32)
+    m = torch.zeros(n, device=dev)
+    v = torch.zeros(n, device=dev)
+    out = torch.zeros(2, device=dev)
+    stream = torch.cuda.current_stream()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    t_stats = t_adam = 0.0
+    for it in range(args.warmup + args.steps):
+        ev[0].record(stream)
+        st.grad_stats(out, stream)
+        ev[1].record(stream)
+        st.adam_step(master, m, v, it + 1, lr=1e-4, grad_scale=1.0 / 32, skip=out[1:], stream=stream)
+        ev[2].record(stream)
+        torch.cuda.synchronize()
+        if it >= args.warmup:
+            t_stats += ev[0].elapsed_time(ev[1])
+            t_adam += ev[1].elapsed_time(ev[2])
+    t_stats /= args.steps
+    t_adam /= args.steps
+    es = 4 if cfg.dtype == "f32" else 2
+    bytes_adam = (28.0 + es) * n      # read g, w, m, v; write w, m, v, param
+    bytes_stats = 4.0 * n
+    ach = bytes_adam / (t_adam * 1e-3) / 1e9
+    res = {"metric": "mini-batch tail: gradient statistics + Adam step (ms)", "value": t_stats + t_adam, "unit": "ms",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": False, "dtype": "f32",
+           "data": "synthetic", "vs_baseline": None,
+           "config": {"workload": cfg.name + " mini-batch tail", "parameters": n, "ms_grad_stats": t_stats,
+                      "ms_adam": t_adam, "grad_stats_gbps": bytes_stats / (t_stats * 1e-3) / 1e9},
+           "roofline": {"kernel": "adam_kernel", "bound": "hbm", "achieved": ach, "peak": flops.MI355X_HBM_PEAK / 1e9,
+                        "unit": "GB/s", "frac": ach / (flops.MI355X_HBM_PEAK / 1e9), "traffic": None}}
+    st.close()
+    return res
 
 
 def _acc(tot, part):

@@ -153,6 +153,40 @@ varuna_status_t varuna_stage_grad_flush(varuna_stage_t* st, void* hip_stream);
 /* Zero-fills grads_f32 (start of a mini-batch) and drops any gathered, unflushed operands. */
 varuna_status_t varuna_stage_grad_accum_reset(varuna_stage_t* st, void* hip_stream);
 
+/* ---- mini-batch tail: one GPU's share of the optimizer step ------------------------------
+ * The paper keeps 16 bytes of state per parameter -- a 16-bit parameter and gradient plus
+ * fp32 master weight, momentum and variance (Background, "Memory optimization") -- and
+ * synchronises an overflow flag / gradient norm over the stages of a pipeline (Enabling Ease
+ * of Programming, "Tracking cross-partition dependencies"; Implementation, "Synchronization
+ * of shared state").  These two calls are the per-GPU part; the reduction across GPUs is the
+ * caller's.  Both return VARUNA_ESTATE while deferred weight gradients are pending (call
+ * varuna_stage_grad_flush first). */
+
+/* out2 (device, 2 floats): [0] = sum of squares of the finite entries of grads_f32,
+ * [1] = number of non-finite entries.  Deterministic (fixed reduction order). */
+varuna_status_t varuna_stage_grad_stats(varuna_stage_t* st, float* out2 /*device*/, void* hip_stream);
+
+typedef struct {
+  float lr, beta1, beta2, eps;
+  float weight_decay;  /* decoupled: w -= lr * weight_decay * w */
+  float grad_scale;    /* multiplies every gradient first (1/loss scale, 1/M, clip factor) */
+  int32_t step;        /* number of this update, >= 1 (bias correction) */
+} varuna_adam_t;
+
+/* One Adam update (Kingma & Ba, Algorithm 1, with decoupled weight decay) over all parameters
+ * of the stage, element order = parameter layout:  g = grad_scale * grads_f32;
+ * m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;
+ * master -= lr * ((m / (1-b1^step)) / (sqrt(v / (1-b2^step)) + eps) + weight_decay * master);
+ * params_out = master rounded to the stage's storage type (RNE).  master_f32, m_f32, v_f32:
+ * caller-owned device buffers of grad_bytes each, 16-byte aligned; params_out: normally the
+ * params buffer given to varuna_stage_create.  If skip_if_nonzero (device, may be NULL)
+ * points to a non-zero value when the kernel runs, nothing is changed (an overflow anywhere
+ * in the pipeline cancels the step). */
+varuna_status_t varuna_stage_adam_step(varuna_stage_t* st, const varuna_adam_t* hp, void* params_out /*device*/,
+                                       float* master_f32 /*device*/, float* m_f32 /*device*/,
+                                       float* v_f32 /*device*/, const float* skip_if_nonzero /*device*/,
+                                       void* hip_stream);
+
 /* Releases the host-side handle.  Device buffers stay with the caller. */
 varuna_status_t varuna_stage_destroy(varuna_stage_t* st);
 

@@ -27,7 +27,7 @@ OP_FWD, OP_DGRAD, OP_WGRAD = 0, 1, 2
 EXPORTS = (
     "varuna_stage_query_sizes", "varuna_stage_param_offset", "varuna_stage_create",
     "varuna_stage_forward", "varuna_stage_backward_recompute", "varuna_stage_grad_accum_reset",
-    "varuna_stage_forward_keep", "varuna_stage_backward_stored",
+    "varuna_stage_forward_keep", "varuna_stage_backward_stored", "varuna_stage_grad_stats", "varuna_stage_adam_step",
     "varuna_stage_grad_flush", "varuna_stage_destroy", "varuna_last_error", "varuna_stage_debug_forward_save",
     "varuna_stage_debug_saved_region", "varuna_stage_profile_enable", "varuna_stage_profile_collect",
     "varuna_op_gemm", "varuna_op_layernorm_fwd", "varuna_op_layernorm_bwd", "varuna_op_colsum",
@@ -39,6 +39,10 @@ class VarunaError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__(f"varuna status {code}: {msg}")
         self.code = code
+
+
+class CAdam(C.Structure):
+    _fields_ = [(n, C.c_float) for n in ("lr", "beta1", "beta2", "eps", "weight_decay", "grad_scale")] + [("step", C.c_int32)]
 
 
 class CConfig(C.Structure):
@@ -78,6 +82,8 @@ def load():
         "varuna_stage_forward_keep": (i32, [vp, i32, vp, vp, vp]),
         "varuna_stage_backward_stored": (i32, [vp, i32, vp, vp, vp]),
         "varuna_stage_grad_accum_reset": (i32, [vp, vp]),
+        "varuna_stage_grad_stats": (i32, [vp, vp, vp]),
+        "varuna_stage_adam_step": (i32, [vp, C.POINTER(CAdam), vp, vp, vp, vp, vp, vp]),
         "varuna_stage_grad_flush": (i32, [vp, vp]),
         "varuna_stage_destroy": (i32, [vp]),
         "varuna_last_error": (C.c_char_p, []),
@@ -191,6 +197,16 @@ class Stage:
 
     def backward_stored(self, mb: int, dy: torch.Tensor, dx: torch.Tensor, stream=None):
         _check(self.lib.varuna_stage_backward_stored(self.handle, mb, _ptr(dy), _ptr(dx), _stream_ptr(stream)))
+
+    def grad_stats(self, out2: torch.Tensor, stream=None):
+        _check(self.lib.varuna_stage_grad_stats(self.handle, _ptr(out2), _stream_ptr(stream)))
+
+    def adam_step(self, master, m, v, step: int, lr: float, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,
+                  grad_scale=1.0, skip=None, params_out=None, stream=None):
+        hp = CAdam(lr, beta1, beta2, eps, weight_decay, grad_scale, step)
+        out = self.params if params_out is None else params_out
+        _check(self.lib.varuna_stage_adam_step(self.handle, C.byref(hp), _ptr(out), _ptr(master), _ptr(m), _ptr(v),
+                                               _ptr(skip), _stream_ptr(stream)))
 
     def grad_accum_reset(self, stream=None):
         _check(self.lib.varuna_stage_grad_accum_reset(self.handle, _stream_ptr(stream)))

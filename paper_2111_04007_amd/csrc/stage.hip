@@ -29,6 +29,7 @@
 #include "gemm_mfma.h"
 #include "gemm_simple.h"
 #include "norm_reduce.h"
+#include "optimizer.h"
 
 using namespace varuna;
 
@@ -114,6 +115,7 @@ struct Workspace {
   size_t saved_begin, saved_end;
   size_t ping[2];                // forward layer outputs (discarded)
   size_t dxn, dctx, delta, partial;
+  size_t stat_partial;           // partial sums of the gradient statistics (doubles)
   size_t total;
 };
 Workspace carve(const Dims& D) {
@@ -143,6 +145,7 @@ Workspace carve(const Dims& D) {
   int64_t widest = 3 * (int64_t)D.h;
   if (D.f > widest) widest = D.f;
   w.partial = take((size_t)colreduce_chunks(D.T) * widest * sizeof(float));
+  w.stat_partial = take((size_t)kStatBlocks * 2 * sizeof(double));
   w.total = o;
   return w;
 }
@@ -640,6 +643,45 @@ varuna_status_t varuna_stage_grad_flush(varuna_stage_t* st, void* hip_stream) {
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   hipError_t e = (st->D.dtype == VARUNA_F32) ? StageOps<float>(st, s).flush() : StageOps<bf16>(st, s).flush();
   return hip_result(e, "varuna_stage_grad_flush");
+}
+
+varuna_status_t varuna_stage_grad_stats(varuna_stage_t* st, float* out2, void* hip_stream) {
+  if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
+  if (!out2) return fail(VARUNA_EINVAL, "NULL output pointer");
+  if (st->pending != 0)
+    return fail(VARUNA_ESTATE, "%d micro-batches of weight gradients are gathered but not accumulated yet: call "
+                "varuna_stage_grad_flush first", st->pending);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const size_t n = st->po.per_layer * st->D.L;
+  Bracket br(st, s, VARUNA_K_OTHER, 0, 4.0 * n);
+  return hip_result(launch_grad_stats(st->grads, n, reinterpret_cast<double*>(st->work + st->ws.stat_partial), out2, s),
+                    "varuna_stage_grad_stats");
+}
+
+varuna_status_t varuna_stage_adam_step(varuna_stage_t* st, const varuna_adam_t* hp, void* params_out, float* master_f32,
+                                       float* m_f32, float* v_f32, const float* skip_if_nonzero, void* hip_stream) {
+  if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
+  if (!hp || !params_out || !master_f32 || !m_f32 || !v_f32) return fail(VARUNA_EINVAL, "NULL pointer");
+  if (hp->step < 1) return fail(VARUNA_EINVAL, "Adam step number must be >= 1, got %d", hp->step);
+  if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f))
+    return fail(VARUNA_EINVAL, "Adam betas must lie in [0, 1)");
+  const void* ptrs[4] = {params_out, master_f32, m_f32, v_f32};
+  for (const void* p : ptrs)
+    if (reinterpret_cast<uintptr_t>(p) % 16 != 0) return fail(VARUNA_EINVAL, "optimizer buffers must be 16-byte aligned");
+  if (st->pending != 0)
+    return fail(VARUNA_ESTATE, "%d micro-batches of weight gradients are gathered but not accumulated yet: call "
+                "varuna_stage_grad_flush first", st->pending);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const size_t n = st->po.per_layer * st->D.L;
+  AdamArgs a{hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, hp->grad_scale,
+             (float)(1.0 / (1.0 - pow((double)hp->beta1, (double)hp->step))),
+             (float)(1.0 / (1.0 - pow((double)hp->beta2, (double)hp->step)))};
+  Bracket br(st, s, VARUNA_K_OTHER, 0, (28.0 + st->D.es) * n);
+  hipError_t e = (st->D.dtype == VARUNA_F32)
+                     ? launch_adam<float>(st->grads, master_f32, m_f32, v_f32, static_cast<float*>(params_out), n, a, skip_if_nonzero, s)
+                     : launch_adam<bf16>(st->grads, master_f32, m_f32, v_f32, static_cast<bf16*>(params_out), n, a, skip_if_nonzero, s);
+  st->kept_mb = -1;  // the parameters changed: kept activations no longer belong to them
+  return hip_result(e, "varuna_stage_adam_step");
 }
 
 varuna_status_t varuna_stage_profile_enable(varuna_stage_t* st, int32_t on) {

@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--calibrate", default="",
                     help="comma-separated micro-batch sizes m: instead of the step benchmark, print F(m), "
                          "recompute+backward(m), keeping-forward(m) and stored-backward(m) per m and the m picked")
+    ap.add_argument("--pipeline-stages", type=int, default=0,
+                    help="with --calibrate: also feed the measured times of the picked m into the schedule simulator "
+                         "for a pipeline of this many stages (the config's M micro-batches) and print the estimates")
     ap.add_argument("--tail", action="store_true",
                     help="instead of the step benchmark, time the mini-batch tail (gradient statistics + Adam "
                          "step over the stage's parameters) and print its HBM roofline")
@@ -99,7 +102,14 @@ def main():
         torch.cuda.set_device(0)
         rows = calibrate.sweep(cfg, ms, n_mb=args.micro_batches or 4, reps=max(1, args.steps))
         pick = calibrate.pick_micro_batch([r["m"] for r in rows], [r["F_per_example_ms"] for r in rows])
-        print(json.dumps({"metric": "calibration: stage compute time per micro-batch size m (ms)", "unit": "ms",
+        sim = None
+        if args.pipeline_stages > 1:
+            from paper_2111_04007_amd import schedule_sim
+            r = next(r for r in rows if r["m"] == pick)
+            sim = schedule_sim.estimate(args.pipeline_stages, cfg.n_micro_batches, r["F_ms"], r["RB_ms"], r["Fkeep_ms"], r["B_ms"])
+            sim.update({"pipeline_stages": args.pipeline_stages, "n_micro_batches": cfg.n_micro_batches, "m": pick,
+                        "note": "compute only: send latency and all-reduce set to 0 (one GPU is measured)"})
+        print(json.dumps({"schedule_estimate": sim, "metric": "calibration: stage compute time per micro-batch size m (ms)", "unit": "ms",
                           "n_gpus": 1, "dtype": cfg.dtype, "data": "synthetic",
                           "config": {"workload": cfg.name + " swept over micro_batch", "n_layers": cfg.n_layers,
                                      "hidden": cfg.hidden, "seq_len": cfg.seq_len},

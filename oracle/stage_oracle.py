@@ -30,6 +30,11 @@ rounded to the storage dtype of the GPU path and widened).  No blocking,
 fusion or reordering: each line below is one formula of the definition.
 Library primitives used as steps: numpy matmul, exp, tanh, sqrt.
 
+Optional dropout (attention probabilities and the two residual branches) takes its masks
+from dropout_oracle.py; pins in tests/test_dropout_oracle_pins.py (the generator's published
+known-answer vectors, mask statistics, finite differences and torch autograd with the same
+masks, recompute regenerating the masks).
+
 Pins (tests/test_oracle_pins.py): central finite differences of every
 gradient, torch-autograd composition of library ops, softmax row sums,
 causal-mask invariants, closed forms (zero query weights, s=1, zero output
@@ -129,8 +134,11 @@ def linear_backward(dy, x, w):
     return dy @ w, dy.T @ x, dy.sum(axis=0)
 
 
-def attention_forward(qkv, sh: StageShape):
+def attention_forward(qkv, sh: StageShape, keep=None):
     """Softmax attention per (batch element, head).
+
+    keep (optional): function (bi, j) -> [s, s] array of dropout factors (scale where the
+    probability is kept, 0 where dropped), applied to the probabilities after the softmax.
 
     qkv is [T, 3h] with column blocks [Q | K | V]; head j owns columns
     j*d..(j+1)*d-1 of each block.  Scores are scaled by 1/sqrt(d) before the
@@ -155,12 +163,12 @@ def attention_forward(qkv, sh: StageShape):
             e = np.exp(sc - sc.max(axis=1, keepdims=True))
             p = e / e.sum(axis=1, keepdims=True)
             probs[(bi, j)] = p
-            ctx[rows, j * d:(j + 1) * d] = p @ v
+            ctx[rows, j * d:(j + 1) * d] = (p if keep is None else p * keep(bi, j)) @ v
     return ctx, probs
 
 
-def attention_backward(dctx, qkv, probs, sh: StageShape):
-    """Gradient of attention_forward w.r.t. qkv. Returns dqkv [T, 3h]."""
+def attention_backward(dctx, qkv, probs, sh: StageShape, keep=None):
+    """Gradient of attention_forward w.r.t. qkv (same dropout factors). Returns dqkv [T, 3h]."""
     h, d, s = sh.hidden, sh.head_dim, sh.seq_len
     dqkv = np.zeros_like(qkv)
     scale = 1.0 / math.sqrt(d)
@@ -172,8 +180,13 @@ def attention_backward(dctx, qkv, probs, sh: StageShape):
             v = qkv[rows, 2 * h + j * d:2 * h + (j + 1) * d]
             p = probs[(bi, j)]
             do = dctx[rows, j * d:(j + 1) * d]
-            dv = p.T @ do
-            dp = do @ v.T
+            if keep is None:
+                dv = p.T @ do
+                dp = do @ v.T
+            else:
+                kp = keep(bi, j)
+                dv = (p * kp).T @ do
+                dp = (do @ v.T) * kp
             ds = p * (dp - (p * dp).sum(axis=1, keepdims=True))
             dqkv[rows, j * d:(j + 1) * d] = (ds @ k) * scale
             dqkv[rows, h + j * d:h + (j + 1) * d] = (ds.T @ q) * scale
@@ -185,30 +198,43 @@ def attention_backward(dctx, qkv, probs, sh: StageShape):
 # one layer
 # --------------------------------------------------------------------------
 
-def layer_forward(x, p: Dict[str, np.ndarray], sh: StageShape):
-    """Forward of one pre-LN block. Returns (y, cache of every intermediate)."""
-    c = {"x": x}
+def _drop_factors(drop, sh: StageShape, layer: int, mb: int):
+    """(keep(bi, j) for the attention probabilities, [T,h] factors of the projection branch,
+    [T,h] factors of the MLP branch) for one layer of one micro-batch, or (None, 1, 1)."""
+    if drop is None:
+        return None, 1.0, 1.0
+    s, a = sh.seq_len, sh.n_heads
+    keep = lambda bi, j: drop.keep_scale(0, layer, mb, (bi * a + j) * s, s, s)
+    return keep, drop.keep_scale(1, layer, mb, 0, sh.tokens, sh.hidden), drop.keep_scale(2, layer, mb, 0, sh.tokens, sh.hidden)
+
+
+def layer_forward(x, p: Dict[str, np.ndarray], sh: StageShape, drop=None, layer: int = 0, mb: int = 0):
+    """Forward of one pre-LN block. Returns (y, cache of every intermediate).  With drop (a
+    dropout_oracle.Dropout) the attention probabilities and the two residual branches are
+    multiplied by their dropout factors, which depend only on (seed, mb, layer, site, element)."""
+    keep, k1, k2 = _drop_factors(drop, sh, layer, mb)
+    c = {"x": x, "keep": keep, "k1": k1, "k2": k2}
     c["xn1"], c["xhat1"], c["rstd1"] = layernorm_forward(x, p["ln1_g"], p["ln1_b"], sh.ln_eps)
     c["qkv"] = linear_forward(c["xn1"], p["wqkv"], p["bqkv"])
-    c["ctx"], c["probs"] = attention_forward(c["qkv"], sh)
-    c["x1"] = x + linear_forward(c["ctx"], p["wo"], p["bo"])
+    c["ctx"], c["probs"] = attention_forward(c["qkv"], sh, keep)
+    c["x1"] = x + k1 * linear_forward(c["ctx"], p["wo"], p["bo"])
     c["xn2"], c["xhat2"], c["rstd2"] = layernorm_forward(c["x1"], p["ln2_g"], p["ln2_b"], sh.ln_eps)
     c["u"] = linear_forward(c["xn2"], p["w1"], p["b1"])
     c["g"] = gelu_tanh(c["u"])
-    y = c["x1"] + linear_forward(c["g"], p["w2"], p["b2"])
+    y = c["x1"] + k2 * linear_forward(c["g"], p["w2"], p["b2"])
     return y, c
 
 
 def layer_backward(dy, p: Dict[str, np.ndarray], c, sh: StageShape):
     """Backward of one block. Returns (dx, dict of parameter gradients)."""
     gr = {}
-    dg, gr["w2"], gr["b2"] = linear_backward(dy, c["g"], p["w2"])
+    dg, gr["w2"], gr["b2"] = linear_backward(dy * c["k2"], c["g"], p["w2"])
     du = dg * gelu_tanh_grad(c["u"])
     dxn2, gr["w1"], gr["b1"] = linear_backward(du, c["xn2"], p["w1"])
     dln2, gr["ln2_g"], gr["ln2_b"] = layernorm_backward(dxn2, c["xhat2"], c["rstd2"], p["ln2_g"])
     dx1 = dy + dln2
-    dctx, gr["wo"], gr["bo"] = linear_backward(dx1, c["ctx"], p["wo"])
-    dqkv = attention_backward(dctx, c["qkv"], c["probs"], sh)
+    dctx, gr["wo"], gr["bo"] = linear_backward(dx1 * c["k1"], c["ctx"], p["wo"])
+    dqkv = attention_backward(dctx, c["qkv"], c["probs"], sh, c["keep"])
     dxn1, gr["wqkv"], gr["bqkv"] = linear_backward(dqkv, c["xn1"], p["wqkv"])
     dln1, gr["ln1_g"], gr["ln1_b"] = layernorm_backward(dxn1, c["xhat1"], c["rstd1"], p["ln1_g"])
     return dx1 + dln1, gr
@@ -218,15 +244,15 @@ def layer_backward(dy, p: Dict[str, np.ndarray], c, sh: StageShape):
 # the stage
 # --------------------------------------------------------------------------
 
-def stage_forward(x, params: Sequence[Dict[str, np.ndarray]], sh: StageShape):
-    """Stage forward for one micro-batch.  x: [T, h].  Returns (y, caches).
+def stage_forward(x, params: Sequence[Dict[str, np.ndarray]], sh: StageShape, drop=None, mb: int = 0):
+    """Stage forward for one micro-batch (number mb).  x: [T, h].  Returns (y, caches).
 
     The caches are what a recompute pass re-derives from the stored stage
     input; the oracle simply keeps them.
     """
     caches = []
-    for p in params:
-        x, c = layer_forward(x, p, sh)
+    for l, p in enumerate(params):
+        x, c = layer_forward(x, p, sh, drop, l, mb)
         caches.append(c)
     return x, caches
 
@@ -239,7 +265,7 @@ def stage_backward(dy, params, caches, sh: StageShape):
     return dy, grads
 
 
-def stage_step(xs, dys, params, sh: StageShape):
+def stage_step(xs, dys, params, sh: StageShape, drop=None):
     """One mini-batch on the stage: all micro-batches, gradients summed.
 
     xs, dys: sequences of [T, h] arrays (stage inputs, upstream gradients).
@@ -248,8 +274,8 @@ def stage_step(xs, dys, params, sh: StageShape):
     """
     ys, dxs = [], []
     acc = [{k: np.zeros(v) for k, v in param_shapes(sh).items()} for _ in params]
-    for x, dy in zip(xs, dys):
-        y, caches = stage_forward(x, params, sh)
+    for mb, (x, dy) in enumerate(zip(xs, dys)):
+        y, caches = stage_forward(x, params, sh, drop, mb)
         dx, gr = stage_backward(dy, params, caches, sh)
         ys.append(y)
         dxs.append(dx)
@@ -259,12 +285,12 @@ def stage_step(xs, dys, params, sh: StageShape):
     return ys, dxs, acc
 
 
-def stage_recompute(x_boundary, params, sh: StageShape):
+def stage_recompute(x_boundary, params, sh: StageShape, drop=None, mb: int = 0):
     """Recompute path: re-derive every intermediate from the stored boundary
     activation alone (Design Overview, High-level architecture).  Same
     arithmetic as stage_forward; kept as a separate entry so a test can
     state the equality."""
-    return stage_forward(np.array(x_boundary, copy=True), params, sh)
+    return stage_forward(np.array(x_boundary, copy=True), params, sh, drop, mb)
 
 
 def rel_l2(a, ref) -> float:

@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--pipeline-stages", type=int, default=0,
                     help="with --calibrate: also feed the measured times of the picked m into the schedule simulator "
                          "for a pipeline of this many stages (the config's M micro-batches) and print the estimates")
+    ap.add_argument("--dropout", type=float, default=0.0,
+                    help="dropout probability on attention probabilities and both residual branches (the headline "
+                         "workload has none; this measures what the counter-based masks cost)")
     ap.add_argument("--tail", action="store_true",
                     help="instead of the step benchmark, time the mini-batch tail (gradient statistics + Adam "
                          "step over the stage's parameters) and print its HBM roofline")
@@ -120,7 +123,7 @@ def main():
         return
     if args.micro_batches:
         cfg = cfg.replace(n_micro_batches=args.micro_batches)
-    cfg = cfg.replace(wgrad_group=max(1, args.wgrad_group))
+    cfg = cfg.replace(wgrad_group=max(1, args.wgrad_group), dropout_p=args.dropout)
     M = cfg.n_micro_batches
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -128,6 +131,8 @@ def main():
 
     params, xs, dys = synth.device_random_stage(cfg, dev)
     st = B.Stage(cfg, dev, params_flat=params)
+    if cfg.dropout_p > 0:
+        st.set_dropout_seed(20211104)
     ys = torch.empty_like(xs)
     dxs = torch.empty_like(xs)
     stream = torch.cuda.current_stream()
@@ -259,9 +264,10 @@ def main():
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {
-            "workload": cfg.name + (" (last-stage variant: no recompute)" if last else ""), "n_layers": cfg.n_layers, "hidden": cfg.hidden, "n_heads": cfg.n_heads,
+            "workload": cfg.name + (" (last-stage variant: no recompute)" if last else "") +
+                        (f" with dropout {cfg.dropout_p}" if cfg.dropout_p > 0 else ""), "n_layers": cfg.n_layers, "hidden": cfg.hidden, "n_heads": cfg.n_heads,
             "seq_len": cfg.seq_len, "micro_batch": cfg.micro_batch, "n_micro_batches": M,
-            "mlp_hidden": cfg.mlp_hidden, "causal": cfg.causal, "wgrad_group": cfg.wgrad_group,
+            "mlp_hidden": cfg.mlp_hidden, "causal": cfg.causal, "wgrad_group": cfg.wgrad_group, "dropout_p": cfg.dropout_p,
             "ms_per_micro_batch": ms_mb, "ms_forward_per_micro_batch": ms_f,
             ("ms_backward_per_micro_batch" if last else "ms_recompute_backward_per_micro_batch"): ms_rb,
             "frac_of_bf16_mfma_peak": frac_peak, "peak_tflops_used": flops.MI355X_BF16_DENSE_PEAK / 1e12,

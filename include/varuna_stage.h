@@ -80,6 +80,8 @@ typedef struct {
   float ln_eps;            /* 0 means 1e-5 */
   int32_t wgrad_group;     /* G: weight-gradient GEMMs are issued once per G micro-batches with
                               reduction length G*T (0 or 1: after every micro-batch) */
+  float dropout_p;         /* dropout probability in [0,1), applied as round(256 p)/256; 0: none.
+                              See varuna_stage_set_dropout_seed. */
 } varuna_stage_config_t;
 
 /* Byte sizes of the four caller-allocated device buffers for this configuration.
@@ -138,6 +140,23 @@ varuna_status_t varuna_stage_forward_keep(varuna_stage_t* st, int32_t mb, const 
 varuna_status_t varuna_stage_backward_stored(varuna_stage_t* st, int32_t mb,
                                              const void* dy_in /*device*/,
                                              void* dx_out /*device*/, void* hip_stream);
+
+/* Dropout (config.dropout_p > 0) acts on the attention probabilities and on the two residual
+ * branches (attention-output projection and MLP output, after their bias, before the add).
+ * The paper's implementation saves and restores the random-number state so that the
+ * recompute pass reproduces the forward pass (Implementation, list of library functions);
+ * here every mask is a pure function of (seed, micro-batch slot mb, layer, site, element),
+ * so forward, recompute and backward regenerate it and nothing is stored.  Generator:
+ * Philox4x32-10, key = (seed mod 2^32, seed div 2^32), counter = (row div 4, column div 4,
+ * site + 256*layer, mb); the byte of element (row, column) is byte (column mod 4), little end
+ * first, of output word (row mod 4); the element is kept iff byte >= thr = round(256 p) and
+ * kept values are multiplied by 256 / (256 - thr).  Sites: 0 = attention probabilities
+ * (row = (batch*heads + head)*seq_len + query, column = key), 1 = projection branch,
+ * 2 = MLP branch (row = token, column = hidden index).
+ * The seed is 0 after create; set a new one per mini-batch.  It must not change between a
+ * forward and the backward of the same slot (VARUNA_ESTATE while any slot is forwarded and
+ * not yet consumed). */
+varuna_status_t varuna_stage_set_dropout_seed(varuna_stage_t* st, uint64_t seed);
 
 /* With wgrad_group G > 1 the operands of the weight-gradient products dW += dY^T X are kept
  * for up to G micro-batches (the workspace holds G slots of them, stacked along the token

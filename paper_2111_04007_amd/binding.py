@@ -27,7 +27,7 @@ OP_FWD, OP_DGRAD, OP_WGRAD = 0, 1, 2
 EXPORTS = (
     "varuna_stage_query_sizes", "varuna_stage_param_offset", "varuna_stage_create",
     "varuna_stage_forward", "varuna_stage_backward_recompute", "varuna_stage_grad_accum_reset",
-    "varuna_stage_forward_keep", "varuna_stage_backward_stored", "varuna_stage_grad_stats", "varuna_stage_adam_step",
+    "varuna_stage_forward_keep", "varuna_stage_backward_stored", "varuna_stage_grad_stats", "varuna_stage_adam_step", "varuna_stage_set_dropout_seed",
     "varuna_stage_grad_flush", "varuna_stage_destroy", "varuna_last_error", "varuna_stage_debug_forward_save",
     "varuna_stage_debug_saved_region", "varuna_stage_profile_enable", "varuna_stage_profile_collect",
     "varuna_op_gemm", "varuna_op_layernorm_fwd", "varuna_op_layernorm_bwd", "varuna_op_colsum",
@@ -48,13 +48,13 @@ class CAdam(C.Structure):
 class CConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "hidden", "n_heads", "seq_len", "micro_batch", "n_micro_batches",
-        "mlp_hidden", "causal", "dtype")] + [("ln_eps", C.c_float), ("wgrad_group", C.c_int32)]
+        "mlp_hidden", "causal", "dtype")] + [("ln_eps", C.c_float), ("wgrad_group", C.c_int32), ("dropout_p", C.c_float)]
 
 
 def c_config(cfg: StageConfig) -> CConfig:
     return CConfig(cfg.n_layers, cfg.hidden, cfg.n_heads, cfg.seq_len, cfg.micro_batch,
                    cfg.n_micro_batches, cfg.mlp_hidden, int(cfg.causal),
-                   F32 if cfg.dtype == "f32" else BF16, cfg.ln_eps, cfg.wgrad_group)
+                   F32 if cfg.dtype == "f32" else BF16, cfg.ln_eps, cfg.wgrad_group, cfg.dropout_p)
 
 
 _lib = None
@@ -82,6 +82,7 @@ def load():
         "varuna_stage_forward_keep": (i32, [vp, i32, vp, vp, vp]),
         "varuna_stage_backward_stored": (i32, [vp, i32, vp, vp, vp]),
         "varuna_stage_grad_accum_reset": (i32, [vp, vp]),
+        "varuna_stage_set_dropout_seed": (i32, [vp, C.c_uint64]),
         "varuna_stage_grad_stats": (i32, [vp, vp, vp]),
         "varuna_stage_adam_step": (i32, [vp, C.POINTER(CAdam), vp, vp, vp, vp, vp, vp]),
         "varuna_stage_grad_flush": (i32, [vp, vp]),
@@ -197,6 +198,9 @@ class Stage:
 
     def backward_stored(self, mb: int, dy: torch.Tensor, dx: torch.Tensor, stream=None):
         _check(self.lib.varuna_stage_backward_stored(self.handle, mb, _ptr(dy), _ptr(dx), _stream_ptr(stream)))
+
+    def set_dropout_seed(self, seed: int):
+        _check(self.lib.varuna_stage_set_dropout_seed(self.handle, seed))
 
     def grad_stats(self, out2: torch.Tensor, stream=None):
         _check(self.lib.varuna_stage_grad_stats(self.handle, _ptr(out2), _stream_ptr(stream)))

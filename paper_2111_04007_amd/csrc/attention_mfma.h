@@ -92,10 +92,10 @@ __device__ __forceinline__ bf16x8 at_pack8(const float* p) {
 // ---------------------------------------------------------------------------
 // forward
 // ---------------------------------------------------------------------------
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
                                                             float* __restrict__ lse, int s, int heads,
-                                                            float scale_log2e) {
+                                                            float scale_log2e, DropArgs drop) {
   using C = AttnCfg<D>;
   __shared__ __attribute__((aligned(16))) bf16 sk[C::TILE];
   __shared__ __attribute__((aligned(16))) bf16 sv[C::TILE];
@@ -171,7 +171,21 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
         p[sb][r] = __builtin_amdgcn_exp2f(p[sb][r] - m_new);
         psum += p[sb][r];
       }
-    l = l * alpha + psum;
+    l = l * alpha + psum;   // the softmax is normalised before the dropout
+    if (DROP) {
+      // this lane's 16 probabilities of a 32-key block are 4 groups of 4 consecutive keys of
+      // ONE mask row (its query): one generator call per group
+      const uint32_t drow = (uint32_t)(((int64_t)bi * heads + head) * s + query);
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const uint32_t w = drop_row_word(drop, drow, (uint32_t)(k0 + sb * 32 + 8 * g + 4 * hf) >> 2);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (!drop_keep(drop, w, e)) p[sb][4 * g + e] = 0.f;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < C::DB; ++i)
 #pragma unroll
@@ -187,7 +201,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
       }
   }
   l += __shfl_xor(l, 32, 64);
-  const float inv = 1.0f / l;
+  const float inv = (DROP ? drop.scale : 1.0f) / l;
   if (lse && hf == 0) lse[((int64_t)bi * heads + head) * s + query] = (m + log2f(l)) * 0.6931471805599453f;
   bf16* crow = ctx + ((int64_t)bi * s + query) * h + head * D;
 #pragma unroll
@@ -204,12 +218,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
 // ---------------------------------------------------------------------------
 // backward, query side: dQ and delta
 // ---------------------------------------------------------------------------
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
                                                                const float* __restrict__ lse,
                                                                const bf16* __restrict__ dctx, bf16* __restrict__ dqkv,
                                                                float* __restrict__ delta, int s, int heads,
-                                                               float scale, float scale_log2e) {
+                                                               float scale, float scale_log2e, DropArgs drop) {
   using C = AttnCfg<D>;
   __shared__ __attribute__((aligned(16))) bf16 sk[C::TILE];
   __shared__ __attribute__((aligned(16))) bf16 sv[C::TILE];
@@ -270,6 +284,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
         sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_row_frag<D>(sk, sb * 32, 16 * t, lane), qf[t], sc, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_row_frag<D>(sv, sb * 32, 16 * t, lane), gf[t], dp, 0, 0, 0);
       }
+      if (DROP) {  // dP = dropout'(dO V^T): same mask words as the forward kernel
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const uint32_t w = drop_row_word(drop, (uint32_t)sidx, (uint32_t)(k0 + sb * 32 + 8 * g + 4 * hf) >> 2);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) dp[4 * g + e] = drop_keep(drop, w, e) ? dp[4 * g + e] * drop.scale : 0.f;
+        }
+      }
       float ds[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -304,11 +326,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
 // ---------------------------------------------------------------------------
 // backward, key side: dK and dV
 // ---------------------------------------------------------------------------
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv, const float* __restrict__ lse,
                                                                 const bf16* __restrict__ dctx,
                                                                 const float* __restrict__ delta, bf16* __restrict__ dqkv,
-                                                                int s, int heads, float scale, float scale_log2e) {
+                                                                int s, int heads, float scale, float scale_log2e,
+                                                                DropArgs drop) {
   using C = AttnCfg<D>;
   __shared__ __attribute__((aligned(16))) bf16 sq[C::TILE];
   __shared__ __attribute__((aligned(16))) bf16 sg[C::TILE];
@@ -379,13 +402,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
         const int ql = sb * 32 + 8 * g + 4 * hf;  // 4 consecutive queries of the tile
         const floatx4 l4 = *reinterpret_cast<const floatx4*>(&sstat[0][ql]);
         const floatx4 d4 = *reinterpret_cast<const floatx4*>(&sstat[1][ql]);
+        uint32_t mw[4];
+        // the 4 consecutive queries are the 4 rows of one mask patch, this lane's key one of its columns
+        if (DROP) drop_patch(drop, (uint32_t)(sbase + q0 + ql) >> 2, (uint32_t)key >> 2, mw);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * g + e;
           float p = __builtin_amdgcn_exp2f(sc[r] * scale_log2e - l4[e]);
           if (need_mask && (q0 + ql + e < key)) p = 0.f;
-          pr[r] = p;
-          ds[r] = p * (dp[r] - d4[e]);
+          float f = 1.0f;
+          if (DROP) f = drop_keep(drop, mw[e], key & 3) ? drop.scale : 0.f;
+          pr[r] = p * f;
+          ds[r] = p * (dp[r] * f - d4[e]);
         }
       }
 #pragma unroll
@@ -419,44 +447,47 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
 // ---------------------------------------------------------------------------
 inline bool attn_mfma_supported(int s, int d) { return (d == 64 || d == 96 || d == 128) && s >= 128 && s % 128 == 0; }
 
-template <int D>
-inline hipError_t attn_fwd_mfma_d(const bf16* qkv, bf16* ctx, float* lse, int b, int s, int heads, int causal, hipStream_t st) {
+template <int D, bool DROP>
+inline hipError_t attn_fwd_mfma_d(const bf16* qkv, bf16* ctx, float* lse, int b, int s, int heads, int causal,
+                                  const DropArgs& drop, hipStream_t st) {
   dim3 grid((unsigned)(s / 128), (unsigned)heads, (unsigned)b);
   const float sl = 1.4426950408889634f / sqrtf((float)D);
-  if (causal) hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, true>), grid, dim3(256), 0, st, qkv, ctx, lse, s, heads, sl);
-  else hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, false>), grid, dim3(256), 0, st, qkv, ctx, lse, s, heads, sl);
+  if (causal) hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, true, DROP>), grid, dim3(256), 0, st, qkv, ctx, lse, s, heads, sl, drop);
+  else hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, false, DROP>), grid, dim3(256), 0, st, qkv, ctx, lse, s, heads, sl, drop);
   return hipGetLastError();
 }
 
 inline hipError_t launch_attention_fwd_mfma(const bf16* qkv, bf16* ctx, float* lse, int b, int s, int heads, int d,
-                                            int causal, hipStream_t st) {
-  if (d == 64) return attn_fwd_mfma_d<64>(qkv, ctx, lse, b, s, heads, causal, st);
-  if (d == 96) return attn_fwd_mfma_d<96>(qkv, ctx, lse, b, s, heads, causal, st);
-  if (d == 128) return attn_fwd_mfma_d<128>(qkv, ctx, lse, b, s, heads, causal, st);
+                                            int causal, const DropArgs& drop, hipStream_t st) {
+  const bool dr = drop.thr != 0;
+  if (d == 64) return dr ? attn_fwd_mfma_d<64, true>(qkv, ctx, lse, b, s, heads, causal, drop, st) : attn_fwd_mfma_d<64, false>(qkv, ctx, lse, b, s, heads, causal, drop, st);
+  if (d == 96) return dr ? attn_fwd_mfma_d<96, true>(qkv, ctx, lse, b, s, heads, causal, drop, st) : attn_fwd_mfma_d<96, false>(qkv, ctx, lse, b, s, heads, causal, drop, st);
+  if (d == 128) return dr ? attn_fwd_mfma_d<128, true>(qkv, ctx, lse, b, s, heads, causal, drop, st) : attn_fwd_mfma_d<128, false>(qkv, ctx, lse, b, s, heads, causal, drop, st);
   return hipErrorInvalidConfiguration;
 }
 
-template <int D>
+template <int D, bool DROP>
 inline hipError_t attn_bwd_mfma_d(const bf16* qkv, const bf16* ctx, const float* lse, const bf16* dctx, bf16* dqkv,
-                                  float* delta, int b, int s, int heads, int causal, hipStream_t st) {
+                                  float* delta, int b, int s, int heads, int causal, const DropArgs& drop, hipStream_t st) {
   dim3 grid((unsigned)(s / 128), (unsigned)heads, (unsigned)b);
   const float sc = 1.0f / sqrtf((float)D), sl = 1.4426950408889634f * sc;
   if (causal) {
-    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, true>), grid, dim3(256), 0, st, qkv, ctx, lse, dctx, dqkv, delta, s, heads, sc, sl);
-    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<D, true>), grid, dim3(256), 0, st, qkv, lse, dctx, delta, dqkv, s, heads, sc, sl);
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, true, DROP>), grid, dim3(256), 0, st, qkv, ctx, lse, dctx, dqkv, delta, s, heads, sc, sl, drop);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<D, true, DROP>), grid, dim3(256), 0, st, qkv, lse, dctx, delta, dqkv, s, heads, sc, sl, drop);
   } else {
-    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, false>), grid, dim3(256), 0, st, qkv, ctx, lse, dctx, dqkv, delta, s, heads, sc, sl);
-    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<D, false>), grid, dim3(256), 0, st, qkv, lse, dctx, delta, dqkv, s, heads, sc, sl);
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, false, DROP>), grid, dim3(256), 0, st, qkv, ctx, lse, dctx, dqkv, delta, s, heads, sc, sl, drop);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<D, false, DROP>), grid, dim3(256), 0, st, qkv, lse, dctx, delta, dqkv, s, heads, sc, sl, drop);
   }
   return hipGetLastError();
 }
 
 inline hipError_t launch_attention_bwd_mfma(const bf16* qkv, const bf16* ctx, const float* lse, const bf16* dctx,
                                             bf16* dqkv, float* delta, int b, int s, int heads, int d, int causal,
-                                            hipStream_t st) {
-  if (d == 64) return attn_bwd_mfma_d<64>(qkv, ctx, lse, dctx, dqkv, delta, b, s, heads, causal, st);
-  if (d == 96) return attn_bwd_mfma_d<96>(qkv, ctx, lse, dctx, dqkv, delta, b, s, heads, causal, st);
-  if (d == 128) return attn_bwd_mfma_d<128>(qkv, ctx, lse, dctx, dqkv, delta, b, s, heads, causal, st);
+                                            const DropArgs& drop, hipStream_t st) {
+  const bool dr = drop.thr != 0;
+  if (d == 64) return dr ? attn_bwd_mfma_d<64, true>(qkv, ctx, lse, dctx, dqkv, delta, b, s, heads, causal, drop, st) : attn_bwd_mfma_d<64, false>(qkv, ctx, lse, dctx, dqkv, delta, b, s, heads, causal, drop, st);
+  if (d == 96) return dr ? attn_bwd_mfma_d<96, true>(qkv, ctx, lse, dctx, dqkv, delta, b, s, heads, causal, drop, st) : attn_bwd_mfma_d<96, false>(qkv, ctx, lse, dctx, dqkv, delta, b, s, heads, causal, drop, st);
+  if (d == 128) return dr ? attn_bwd_mfma_d<128, true>(qkv, ctx, lse, dctx, dqkv, delta, b, s, heads, causal, drop, st) : attn_bwd_mfma_d<128, false>(qkv, ctx, lse, dctx, dqkv, delta, b, s, heads, causal, drop, st);
   return hipErrorInvalidConfiguration;
 }
 

@@ -17,7 +17,7 @@ constexpr int ATS_MAX_D = 256;
 template <typename T>
 __global__ void attention_fwd_simple_kernel(const T* __restrict__ qkv, T* __restrict__ ctx,
                                             float* __restrict__ lse, int s, int heads, int d,
-                                            int causal, float scale) {
+                                            int causal, float scale, DropArgs drop) {
   extern __shared__ float smem[];
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int nw = blockDim.x / kWave;
@@ -44,13 +44,15 @@ __global__ void attention_fwd_simple_kernel(const T* __restrict__ qkv, T* __rest
   }
   mx = wave_max(mx);
   float sum = 0.f;
+  const uint32_t drow = (uint32_t)(((int64_t)bi * heads + j) * s + i);  // row of the dropout mask
   for (int k = lane; k < nk; k += kWave) {
     float e = expf(p[k] - mx);
+    sum += e;   // the softmax is normalised before the dropout
+    if (drop.thr != 0 && !drop_keep(drop, drop_row_word(drop, drow, (uint32_t)k >> 2), k & 3)) e = 0.f;
     p[k] = e;
-    sum += e;
   }
   sum = wave_sum(sum);
-  const float inv = 1.0f / sum;
+  const float inv = (drop.thr != 0 ? drop.scale : 1.0f) / sum;
   if (lse && lane == 0) lse[((int64_t)bi * heads + j) * s + i] = mx + logf(sum);
   __builtin_amdgcn_wave_barrier();
   T* crow = ctx + ((int64_t)bi * s + i) * h + j * d;
@@ -69,7 +71,7 @@ __global__ void attention_bwd_dq_simple_kernel(const T* __restrict__ qkv, const 
                                                const float* __restrict__ lse,
                                                const T* __restrict__ dctx, T* __restrict__ dqkv,
                                                float* __restrict__ delta, int s, int heads, int d,
-                                               int causal, float scale) {
+                                               int causal, float scale, DropArgs drop) {
   extern __shared__ float smem[];
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int nw = blockDim.x / kWave;
@@ -105,6 +107,8 @@ __global__ void attention_bwd_dq_simple_kernel(const T* __restrict__ qkv, const 
       dp = fmaf(go[e], to_f32(vrow[e]), dp);
     }
     float pr = expf(dot * scale - l);
+    if (drop.thr != 0)
+      dp = drop_keep(drop, drop_row_word(drop, (uint32_t)sidx, (uint32_t)k >> 2), k & 3) ? dp * drop.scale : 0.f;
     ds[k] = pr * (dp - dl);
   }
   __builtin_amdgcn_wave_barrier();
@@ -124,7 +128,7 @@ __global__ void attention_bwd_dkv_simple_kernel(const T* __restrict__ qkv,
                                                 const T* __restrict__ dctx,
                                                 const float* __restrict__ delta,
                                                 T* __restrict__ dqkv, int s, int heads, int d,
-                                                int causal, float scale) {
+                                                int causal, float scale, DropArgs drop) {
   extern __shared__ float smem[];
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int nw = blockDim.x / kWave;
@@ -154,8 +158,11 @@ __global__ void attention_bwd_dkv_simple_kernel(const T* __restrict__ qkv,
       dp = fmaf(to_f32(grow[e]), vv[e], dp);
     }
     float pr = expf(dot * scale - lse[sbase + i]);
-    pp[i] = pr;
-    ds[i] = pr * (dp - delta[sbase + i]);
+    float f = 1.0f;
+    if (drop.thr != 0)
+      f = drop_keep(drop, drop_row_word(drop, (uint32_t)(sbase + i), (uint32_t)k >> 2), k & 3) ? drop.scale : 0.f;
+    pp[i] = pr * f;
+    ds[i] = pr * (dp * f - delta[sbase + i]);
   }
   __builtin_amdgcn_wave_barrier();
   T* dk = dqkv + ((int64_t)bi * s + k) * ld + h + j * d;
@@ -182,20 +189,20 @@ inline int ats_waves(size_t bytes_per_wave) {
 
 template <typename T>
 inline hipError_t launch_attention_fwd_simple(const T* qkv, T* ctx, float* lse, int b, int s,
-                                              int heads, int d, int causal, hipStream_t st) {
+                                              int heads, int d, int causal, const DropArgs& drop, hipStream_t st) {
   const int nw = ats_waves((size_t)(d + s) * sizeof(float));
   if (nw == 0) return hipErrorInvalidValue;
   const size_t sm = (size_t)nw * (d + s) * sizeof(float);
   dim3 grid((unsigned)((s + nw - 1) / nw), (unsigned)heads, (unsigned)b);
   hipLaunchKernelGGL((attention_fwd_simple_kernel<T>), grid, dim3(nw * kWave), sm, st, qkv, ctx, lse,
-                     s, heads, d, causal, 1.0f / sqrtf((float)d));
+                     s, heads, d, causal, 1.0f / sqrtf((float)d), drop);
   return hipGetLastError();
 }
 
 template <typename T>
 inline hipError_t launch_attention_bwd_simple(const T* qkv, const T* ctx, const float* lse,
                                               const T* dctx, T* dqkv, float* delta, int b, int s,
-                                              int heads, int d, int causal, hipStream_t st) {
+                                              int heads, int d, int causal, const DropArgs& drop, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)d);
   {
     const int nw = ats_waves((size_t)(2 * d + s) * sizeof(float));
@@ -203,7 +210,7 @@ inline hipError_t launch_attention_bwd_simple(const T* qkv, const T* ctx, const 
     const size_t sm = (size_t)nw * (2 * d + s) * sizeof(float);
     dim3 grid((unsigned)((s + nw - 1) / nw), (unsigned)heads, (unsigned)b);
     hipLaunchKernelGGL((attention_bwd_dq_simple_kernel<T>), grid, dim3(nw * kWave), sm, st, qkv, ctx,
-                       lse, dctx, dqkv, delta, s, heads, d, causal, scale);
+                       lse, dctx, dqkv, delta, s, heads, d, causal, scale, drop);
   }
   {
     const int nw = ats_waves((size_t)(2 * d + 2 * s) * sizeof(float));
@@ -211,7 +218,7 @@ inline hipError_t launch_attention_bwd_simple(const T* qkv, const T* ctx, const 
     const size_t sm = (size_t)nw * (2 * d + 2 * s) * sizeof(float);
     dim3 grid((unsigned)((s + nw - 1) / nw), (unsigned)heads, (unsigned)b);
     hipLaunchKernelGGL((attention_bwd_dkv_simple_kernel<T>), grid, dim3(nw * kWave), sm, st, qkv, lse,
-                       dctx, delta, dqkv, s, heads, d, causal, scale);
+                       dctx, delta, dqkv, s, heads, d, causal, scale, drop);
   }
   return hipGetLastError();
 }

@@ -46,6 +46,53 @@ __device__ __forceinline__ float gelu_tanh_grad_f(float u) {
   return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * dinner;
 }
 
+// ---- dropout masks --------------------------------------------------------------------
+// Masks are a pure function of (seed, micro-batch, layer, site, element), so the recompute
+// pass regenerates exactly the masks of the forward pass it repeats (the paper's
+// implementation saves and restores the generator state for that; Implementation, list of
+// library functions).  Generator: Philox4x32-10 (Salmon et al., SC'11).
+//   key = (seed low, seed high); counter = (row / 4, column / 4, site + 256 * layer, mb):
+//   one call covers a 4 x 4 patch of a site's matrix; the element's byte is byte (column % 4),
+//   little end first, of output word (row % 4); an element is kept iff byte >= thr
+//   (thr = round(256 p)) and kept values are multiplied by scale = 256 / (256 - thr).
+// Sites: 0 attention probabilities (row = (batch * heads + head) * s + query, column = key),
+// 1 attention-output projection before the residual add, 2 MLP output before the residual
+// add (row = token, column = hidden index).
+struct DropArgs {
+  uint32_t thr;         // 0: no dropout at this site
+  float scale;
+  uint32_t key0, key1;
+  uint32_t tag;         // site + 256 * layer
+  uint32_t mb;
+};
+enum : uint32_t { DROP_SITE_ATTN = 0, DROP_SITE_PROJ = 1, DROP_SITE_MLP = 2 };
+
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    c0 = hi1 ^ c1 ^ k0; c1 = lo1; c2 = hi0 ^ c3 ^ k1; c3 = lo0;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+// The four words of the patch (row_patch, col_patch): word i holds the bytes of row 4*row_patch + i.
+__device__ __forceinline__ void drop_patch(const DropArgs& d, uint32_t row_patch, uint32_t col_patch, uint32_t w[4]) {
+  philox4x32_10(row_patch, col_patch, d.tag, d.mb, d.key0, d.key1, w);
+}
+// The word of one row: bytes of columns 4*col_patch .. +3.
+__device__ __forceinline__ uint32_t drop_row_word(const DropArgs& d, uint32_t row, uint32_t col_patch) {
+  uint32_t w[4];
+  drop_patch(d, row >> 2, col_patch, w);
+  const uint32_t i = row & 3;
+  return i == 0 ? w[0] : (i == 1 ? w[1] : (i == 2 ? w[2] : w[3]));
+}
+__device__ __forceinline__ bool drop_keep(const DropArgs& d, uint32_t word, int byte) {
+  return ((word >> (8 * byte)) & 0xffu) >= d.thr;
+}
+
 // Epilogue selectors shared by every GEMM kernel.
 enum EpiMode : int {
   EPI_BIAS = 0,       // out = acc + bias[n]
@@ -64,6 +111,7 @@ struct EpiArgs {
   T* aux_out;        // [M,N] pre-GeLU u, may be null
   float* out_f32;    // [M,N] accumulator for EPI_ACCUM_F32
   int64_t ldc;       // row pitch of out / aux_in / aux_out / out_f32 in elements
+  DropArgs drop;     // EPI_BIAS_RES only: out = aux_in + dropout(acc + bias)
 };
 
 // One output element.
@@ -77,7 +125,10 @@ __device__ __forceinline__ void epilogue_store(const EpiArgs<T>& e, int64_t m, i
     if (e.aux_out) e.aux_out[idx] = from_f32<T>(u);
     e.out[idx] = from_f32<T>(gelu_tanh_f(u));
   } else if (MODE == EPI_BIAS_RES) {
-    e.out[idx] = from_f32<T>(acc + to_f32(e.bias[n]) + to_f32(e.aux_in[idx]));
+    float v = acc + to_f32(e.bias[n]);
+    if (e.drop.thr != 0)
+      v = drop_keep(e.drop, drop_row_word(e.drop, (uint32_t)m, (uint32_t)(n >> 2)), (int)(n & 3)) ? v * e.drop.scale : 0.f;
+    e.out[idx] = from_f32<T>(v + to_f32(e.aux_in[idx]));
   } else if (MODE == EPI_DGELU) {
     e.out[idx] = from_f32<T>(acc * gelu_tanh_grad_f(to_f32(e.aux_in[idx])));
   } else if (MODE == EPI_PLAIN) {

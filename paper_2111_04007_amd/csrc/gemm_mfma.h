@@ -61,6 +61,11 @@ __device__ __forceinline__ void mg_epilogue4(const EpiArgs<bf16>& e, int64_t m, 
     for (int i = 0; i < 4; ++i) o[i] = gelu_tanh_f(o[i]);
   }
   if (MODE == EPI_BIAS_RES) {
+    if (e.drop.thr != 0) {  // n is a multiple of 4: one patch row covers the four columns
+      const uint32_t w = drop_row_word(e.drop, (uint32_t)m, (uint32_t)(n >> 2));
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[i] = drop_keep(e.drop, w, i) ? o[i] * e.drop.scale : 0.f;
+    }
     bf16x4 rv = *reinterpret_cast<const bf16x4*>(e.aux_in + idx);
 #pragma unroll
     for (int i = 0; i < 4; ++i) o[i] += (float)rv[i];
@@ -99,6 +104,15 @@ __device__ __forceinline__ void mg_epilogue8(const EpiArgs<bf16>& e, int64_t m, 
     for (int i = 0; i < 8; ++i) o[i] = gelu_tanh_f(o[i]);
   }
   if (MODE == EPI_BIAS_RES) {
+    if (e.drop.thr != 0) {  // n is a multiple of 8: two patches of this row
+      const uint32_t w0 = drop_row_word(e.drop, (uint32_t)m, (uint32_t)(n >> 2));
+      const uint32_t w1 = drop_row_word(e.drop, (uint32_t)m, (uint32_t)(n >> 2) + 1);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        o[i] = drop_keep(e.drop, w0, i) ? o[i] * e.drop.scale : 0.f;
+        o[4 + i] = drop_keep(e.drop, w1, i) ? o[4 + i] * e.drop.scale : 0.f;
+      }
+    }
     const bf16x8 rv = *reinterpret_cast<const bf16x8*>(e.aux_in + idx);
 #pragma unroll
     for (int i = 0; i < 8; ++i) o[i] += (float)rv[i];

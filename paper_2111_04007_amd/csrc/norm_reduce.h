@@ -224,4 +224,33 @@ inline hipError_t launch_colsum(const T* a, float* out, float* partial, int64_t 
   return hipGetLastError();
 }
 
+// out = dropout(in) with the mask of one site (backward of a residual-branch dropout: the
+// gradient that enters the branch's GEMMs and bias reduction).  One thread per 4 columns of a
+// row = one mask word.
+template <typename T>
+__global__ __launch_bounds__(256) void dropout_apply_kernel(const T* __restrict__ in, T* __restrict__ out, int64_t rows,
+                                                            int64_t cols, DropArgs drop) {
+  const int64_t cpr = (cols + 3) / 4;  // column patches per row
+  const int64_t total = rows * cpr;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = i / cpr, cp = i % cpr;
+    const uint32_t w = drop_row_word(drop, (uint32_t)r, (uint32_t)cp);
+    const int64_t base = r * cols + cp * 4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (cp * 4 + e < cols)
+        out[base + e] = drop_keep(drop, w, e) ? from_f32<T>(to_f32(in[base + e]) * drop.scale) : from_f32<T>(0.f);
+  }
+}
+
+template <typename T>
+inline hipError_t launch_dropout_apply(const T* in, T* out, int64_t rows, int64_t cols, const DropArgs& drop, hipStream_t st) {
+  const int64_t total = rows * ((cols + 3) / 4);
+  int64_t nblk = (total + 255) / 256;
+  if (nblk > 16384) nblk = 16384;
+  if (nblk < 1) nblk = 1;
+  hipLaunchKernelGGL((dropout_apply_kernel<T>), dim3((unsigned)nblk), dim3(256), 0, st, in, out, rows, cols, drop);
+  return hipGetLastError();
+}
+
 }  // namespace varuna

@@ -59,6 +59,8 @@ struct Dims {
   float eps;
   int64_t T, E, F;  // tokens, T*h, T*f
   size_t es;        // bytes per activation / parameter element
+  uint32_t drop_thr;  // dropout: an element is kept iff its random byte >= drop_thr (0: no dropout)
+  float drop_scale;   // 256 / (256 - drop_thr)
 };
 
 varuna_status_t make_dims(const varuna_stage_config_t* c, Dims* o) {
@@ -80,6 +82,11 @@ varuna_status_t make_dims(const varuna_stage_config_t* c, Dims* o) {
   o->eps = c->ln_eps > 0.0f ? c->ln_eps : 1e-5f;
   o->T = (int64_t)o->b * o->s; o->E = o->T * o->h; o->F = o->T * o->f;
   o->es = c->dtype == VARUNA_F32 ? 4 : 2;
+  if (!(c->dropout_p >= 0.0f) || !(c->dropout_p < 1.0f)) return fail(VARUNA_EINVAL, "dropout_p must lie in [0, 1)");
+  o->drop_thr = (uint32_t)lrintf(256.0f * c->dropout_p);
+  if (o->drop_thr > 255) return fail(VARUNA_EINVAL, "dropout_p %g rounds to probability 1", (double)c->dropout_p);
+  o->drop_scale = 256.0f / (256.0f - (float)o->drop_thr);
+  if ((int64_t)o->b * o->a * o->s >= (1ll << 32)) return fail(VARUNA_EUNSUPPORTED, "batch * heads * seq_len exceeds 2^32");
   if (o->s > ATS_MAX_S) return fail(VARUNA_EUNSUPPORTED, "seq_len %d exceeds the supported maximum %d", o->s, ATS_MAX_S);
   if (o->d > ATS_MAX_D) return fail(VARUNA_EUNSUPPORTED, "head dim %d exceeds the supported maximum %d", o->d, ATS_MAX_D);
   if (o->T > (1ll << 24) || (int64_t)o->h > (1 << 20) || (int64_t)o->f > (1 << 22))
@@ -108,6 +115,7 @@ struct LayerArea {
   size_t stats1, qkv, lse, x1, stats2, u, y;   // one copy
   size_t xn1, ctx, xn2, g;                     // rings written by the recompute pass
   size_t dy, du, dx1, dqkv;                    // rings written by the backward pass
+  size_t dyd, dx1d;                            // with dropout: dy, dx1 after the branch masks (rings)
 };
 struct Workspace {
   std::vector<LayerArea> layer;  // per layer: saved activations and backward rings
@@ -137,6 +145,8 @@ Workspace carve(const Dims& D) {
   for (int l = 0; l < D.L; ++l) {
     LayerArea& a = w.layer[l];
     a.dy = take((size_t)D.G * E); a.du = take((size_t)D.G * F); a.dx1 = take((size_t)D.G * E); a.dqkv = take((size_t)D.G * 3 * E);
+    if (D.drop_thr) { a.dyd = take((size_t)D.G * E); a.dx1d = take((size_t)D.G * E); }
+    else { a.dyd = a.dy; a.dx1d = a.dx1; }
   }
   w.fwd = area(1, false);
   w.ping[0] = take(E); w.ping[1] = take(E);
@@ -166,6 +176,7 @@ struct varuna_stage {
   int pending = 0;  // micro-batches whose weight-gradient GEMMs have not been issued yet
   int kept_mb = -1;  // micro-batch whose internals forward_keep left in the layer areas (-1: none)
   int kept_slot = 0; // ring slot they were written to
+  uint64_t seed = 0;  // dropout seed (varuna_stage_set_dropout_seed)
   // profiler
   bool prof_on = false;
   std::vector<hipEvent_t> ev;  // pairs
@@ -239,37 +250,39 @@ template <> struct GemmDispatch<bf16> {
 };
 
 template <typename T> struct AttnDispatch {
-  static hipError_t fwd(int variant, const T* qkv, T* ctx, float* lse, int b, int s, int a, int d, int causal, hipStream_t st) {
+  static hipError_t fwd(int variant, const T* qkv, T* ctx, float* lse, int b, int s, int a, int d, int causal,
+                        const DropArgs& drop, hipStream_t st) {
     (void)variant;
-    return launch_attention_fwd_simple<T>(qkv, ctx, lse, b, s, a, d, causal, st);
+    return launch_attention_fwd_simple<T>(qkv, ctx, lse, b, s, a, d, causal, drop, st);
   }
   static hipError_t bwd(int variant, const T* qkv, const T* ctx, const float* lse, const T* dctx, T* dqkv,
-                        float* delta, int b, int s, int a, int d, int causal, hipStream_t st) {
+                        float* delta, int b, int s, int a, int d, int causal, const DropArgs& drop, hipStream_t st) {
     (void)variant;
-    return launch_attention_bwd_simple<T>(qkv, ctx, lse, dctx, dqkv, delta, b, s, a, d, causal, st);
+    return launch_attention_bwd_simple<T>(qkv, ctx, lse, dctx, dqkv, delta, b, s, a, d, causal, drop, st);
   }
 };
 
 template <> struct AttnDispatch<bf16> {
   // variant 0: library's choice; -1: simple kernels; 1: MFMA kernels
-  static hipError_t fwd(int variant, const bf16* qkv, bf16* ctx, float* lse, int b, int s, int a, int d, int causal, hipStream_t st) {
+  static hipError_t fwd(int variant, const bf16* qkv, bf16* ctx, float* lse, int b, int s, int a, int d, int causal,
+                        const DropArgs& drop, hipStream_t st) {
     int v = variant;
     if (v == 0) v = attn_mfma_supported(s, d) ? 1 : -1;
     if (v == 1) {
       if (!attn_mfma_supported(s, d)) return hipErrorInvalidConfiguration;
-      return launch_attention_fwd_mfma(qkv, ctx, lse, b, s, a, d, causal, st);
+      return launch_attention_fwd_mfma(qkv, ctx, lse, b, s, a, d, causal, drop, st);
     }
-    return launch_attention_fwd_simple<bf16>(qkv, ctx, lse, b, s, a, d, causal, st);
+    return launch_attention_fwd_simple<bf16>(qkv, ctx, lse, b, s, a, d, causal, drop, st);
   }
   static hipError_t bwd(int variant, const bf16* qkv, const bf16* ctx, const float* lse, const bf16* dctx, bf16* dqkv,
-                        float* delta, int b, int s, int a, int d, int causal, hipStream_t st) {
+                        float* delta, int b, int s, int a, int d, int causal, const DropArgs& drop, hipStream_t st) {
     int v = variant;
     if (v == 0) v = attn_mfma_supported(s, d) ? 1 : -1;
     if (v == 1) {
       if (!attn_mfma_supported(s, d)) return hipErrorInvalidConfiguration;
-      return launch_attention_bwd_mfma(qkv, ctx, lse, dctx, dqkv, delta, b, s, a, d, causal, st);
+      return launch_attention_bwd_mfma(qkv, ctx, lse, dctx, dqkv, delta, b, s, a, d, causal, drop, st);
     }
-    return launch_attention_bwd_simple<bf16>(qkv, ctx, lse, dctx, dqkv, delta, b, s, a, d, causal, st);
+    return launch_attention_bwd_simple<bf16>(qkv, ctx, lse, dctx, dqkv, delta, b, s, a, d, causal, drop, st);
   }
 };
 
@@ -288,9 +301,15 @@ struct StageOps {
   float* grad(int l, int which) const { return S->grads + (size_t)l * S->po.per_layer + S->po.off[which]; }
   template <typename U> U* wsp(size_t off) const { return reinterpret_cast<U*>(S->work + off); }
 
+  // Dropout arguments of `site` in layer l for micro-batch mb (thr = 0 when the stage has no dropout).
+  DropArgs drop_args(uint32_t site, int l, int mb) const {
+    return DropArgs{D.drop_thr, D.drop_scale, (uint32_t)(S->seed & 0xffffffffu), (uint32_t)(S->seed >> 32),
+                    site + 256u * (uint32_t)l, (uint32_t)mb};
+  }
+
   hipError_t gemm(int cls, int op, int mode, int64_t M, int64_t N, int64_t K, const T* a, const T* b, const T* bias,
-                  const T* aux_in, T* out, T* aux_out, float* out_f32) {
-    EpiArgs<T> e{bias, aux_in, out, aux_out, out_f32, N};
+                  const T* aux_in, T* out, T* aux_out, float* out_f32, const DropArgs& drop = DropArgs{}) {
+    EpiArgs<T> e{bias, aux_in, out, aux_out, out_f32, N, drop};
     double bytes = (double)(M * K + N * K) * sizeof(T) + (double)M * N * (out_f32 ? 8.0 : (double)sizeof(T));
     Bracket br(S, st, cls, 2.0 * M * N * K, bytes);
     return GemmDispatch<T>::run(op, mode, 0, M, N, K, a, b, e, st);
@@ -303,7 +322,7 @@ struct StageOps {
 
   // One layer forward.  rs: ring slot of the wgrad operands (xn1, ctx, xn2, g).
   // save: also store stats, lse, u.  skip_mlp2: stop after GeLU.
-  hipError_t layer_forward(int l, const T* x, T* y, const LayerArea& A, int rs, bool save, bool skip_mlp2) {
+  hipError_t layer_forward(int l, int mb, const T* x, T* y, const LayerArea& A, int rs, bool save, bool skip_mlp2) {
     hipError_t e;
     const int64_t T_ = D.T;
     T* xn1 = wsp<T>(A.xn1) + (size_t)rs * D.E; T* qkv = wsp<T>(A.qkv); T* ctx = wsp<T>(A.ctx) + (size_t)rs * D.E;
@@ -319,16 +338,16 @@ struct StageOps {
     if ((e = gemm(VARUNA_K_GEMM_FWD, GEMM_FWD, EPI_BIAS, T_, 3 * D.h, D.h, xn1, param(l, VARUNA_P_WQKV), param(l, VARUNA_P_BQKV), nullptr, qkv, nullptr, nullptr))) return e;
     {
       Bracket br(S, st, VARUNA_K_ATTN_FWD, attn_flops_fwd(), 4.0 * D.E * sizeof(T));
-      if ((e = AttnDispatch<T>::fwd(0, qkv, ctx, lse, D.b, D.s, D.a, D.d, D.causal, st))) return e;
+      if ((e = AttnDispatch<T>::fwd(0, qkv, ctx, lse, D.b, D.s, D.a, D.d, D.causal, drop_args(DROP_SITE_ATTN, l, mb), st))) return e;
     }
-    if ((e = gemm(VARUNA_K_GEMM_FWD, GEMM_FWD, EPI_BIAS_RES, T_, D.h, D.h, ctx, param(l, VARUNA_P_WO), param(l, VARUNA_P_BO), x, x1, nullptr, nullptr))) return e;
+    if ((e = gemm(VARUNA_K_GEMM_FWD, GEMM_FWD, EPI_BIAS_RES, T_, D.h, D.h, ctx, param(l, VARUNA_P_WO), param(l, VARUNA_P_BO), x, x1, nullptr, nullptr, drop_args(DROP_SITE_PROJ, l, mb)))) return e;
     {
       Bracket br(S, st, VARUNA_K_LN_FWD, 0, 2.0 * D.E * sizeof(T));
       if ((e = launch_layernorm_fwd<T>(x1, param(l, VARUNA_P_LN2_G), param(l, VARUNA_P_LN2_B), xn2, stats2, T_, D.h, D.eps, st))) return e;
     }
     if ((e = gemm(VARUNA_K_GEMM_FWD, GEMM_FWD, EPI_BIAS_GELU, T_, D.f, D.h, xn2, param(l, VARUNA_P_W1), param(l, VARUNA_P_B1), nullptr, g, save ? u : nullptr, nullptr))) return e;
     if (skip_mlp2) return hipSuccess;
-    return gemm(VARUNA_K_GEMM_FWD, GEMM_FWD, EPI_BIAS_RES, T_, D.h, D.f, g, param(l, VARUNA_P_W2), param(l, VARUNA_P_B2), x1, y, nullptr, nullptr);
+    return gemm(VARUNA_K_GEMM_FWD, GEMM_FWD, EPI_BIAS_RES, T_, D.h, D.f, g, param(l, VARUNA_P_W2), param(l, VARUNA_P_B2), x1, y, nullptr, nullptr, drop_args(DROP_SITE_MLP, l, mb));
   }
 
   hipError_t colsum(const T* a, float* out, int64_t n) {
@@ -340,7 +359,7 @@ struct StageOps {
   // already sits in slot rs of the layer's dy ring; dx: gradient of its input.  The four
   // weight-gradient GEMMs are not issued here (see flush_wgrads): this pass leaves their
   // operands in the rings.
-  hipError_t layer_backward(int l, const T* x, T* dx, const LayerArea& A, int rs) {
+  hipError_t layer_backward(int l, int mb, const T* x, T* dx, const LayerArea& A, int rs) {
     hipError_t e;
     const int64_t T_ = D.T;
     const Workspace& W = S->ws;
@@ -354,9 +373,19 @@ struct StageOps {
     T* dxn = wsp<T>(W.dxn); T* dctx = wsp<T>(W.dctx);
     float* delta = wsp<float>(W.delta); float* partial = wsp<float>(W.partial);
 
-    // MLP2: du = (dy W2) * GeLU'(u); db2 += colsum(dy)
-    if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_DGELU, T_, D.f, D.h, dy, param(l, VARUNA_P_W2), nullptr, u, du, nullptr, nullptr))) return e;
-    if ((e = colsum(dy, grad(l, VARUNA_P_B2), D.h))) return e;
+    // With dropout the gradient entering a residual branch is the masked one (dyd, dx1d); the
+    // residual path itself keeps dy / dx1.
+    const bool dr = D.drop_thr != 0;
+    const T* dyd = dy;
+    if (dr) {
+      T* o = wsp<T>(A.dyd) + (size_t)rs * D.E;
+      Bracket br(S, st, VARUNA_K_OTHER, 0, 2.0 * D.E * sizeof(T));
+      if ((e = launch_dropout_apply<T>(dy, o, T_, D.h, drop_args(DROP_SITE_MLP, l, mb), st))) return e;
+      dyd = o;
+    }
+    // MLP2: du = (dyd W2) * GeLU'(u); db2 += colsum(dyd)
+    if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_DGELU, T_, D.f, D.h, dyd, param(l, VARUNA_P_W2), nullptr, u, du, nullptr, nullptr))) return e;
+    if ((e = colsum(dyd, grad(l, VARUNA_P_B2), D.h))) return e;
     // MLP1: dxn2 = du W1; db1 += colsum(du)
     if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_PLAIN, T_, D.h, D.f, du, param(l, VARUNA_P_W1), nullptr, nullptr, dxn, nullptr, nullptr))) return e;
     if ((e = colsum(du, grad(l, VARUNA_P_B1), D.f))) return e;
@@ -365,13 +394,20 @@ struct StageOps {
       Bracket br(S, st, VARUNA_K_LN_BWD, 0, 6.0 * D.E * sizeof(T));
       if ((e = launch_layernorm_bwd<T>(dxn, x1, stats2, param(l, VARUNA_P_LN2_G), dy, dx1, grad(l, VARUNA_P_LN2_G), grad(l, VARUNA_P_LN2_B), partial, T_, D.h, st))) return e;
     }
-    // proj: dctx = dx1 Wo; dbo += colsum(dx1)
-    if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_PLAIN, T_, D.h, D.h, dx1, param(l, VARUNA_P_WO), nullptr, nullptr, dctx, nullptr, nullptr))) return e;
-    if ((e = colsum(dx1, grad(l, VARUNA_P_BO), D.h))) return e;
+    const T* dx1d = dx1;
+    if (dr) {
+      T* o = wsp<T>(A.dx1d) + (size_t)rs * D.E;
+      Bracket br(S, st, VARUNA_K_OTHER, 0, 2.0 * D.E * sizeof(T));
+      if ((e = launch_dropout_apply<T>(dx1, o, T_, D.h, drop_args(DROP_SITE_PROJ, l, mb), st))) return e;
+      dx1d = o;
+    }
+    // proj: dctx = dx1d Wo; dbo += colsum(dx1d)
+    if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_PLAIN, T_, D.h, D.h, dx1d, param(l, VARUNA_P_WO), nullptr, nullptr, dctx, nullptr, nullptr))) return e;
+    if ((e = colsum(dx1d, grad(l, VARUNA_P_BO), D.h))) return e;
     // attention
     {
       Bracket br(S, st, VARUNA_K_ATTN_BWD, 2.5 * attn_flops_fwd(), 9.0 * D.E * sizeof(T));
-      if ((e = AttnDispatch<T>::bwd(0, qkv, ctx, lse, dctx, dqkv, delta, D.b, D.s, D.a, D.d, D.causal, st))) return e;
+      if ((e = AttnDispatch<T>::bwd(0, qkv, ctx, lse, dctx, dqkv, delta, D.b, D.s, D.a, D.d, D.causal, drop_args(DROP_SITE_ATTN, l, mb), st))) return e;
     }
     // QKV: dxn1 = dqkv Wqkv; dbqkv += colsum(dqkv)
     if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_PLAIN, T_, D.h, 3 * D.h, dqkv, param(l, VARUNA_P_WQKV), nullptr, nullptr, dxn, nullptr, nullptr))) return e;
@@ -392,9 +428,9 @@ struct StageOps {
     const int64_t K = (int64_t)cnt * D.T;
     for (int l = D.L - 1; l >= 0; --l) {
       const LayerArea& A = S->ws.layer[l];
-      if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.h, D.f, K, wsp<T>(A.dy), wsp<T>(A.g), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_W2)))) return e;
+      if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.h, D.f, K, wsp<T>(A.dyd), wsp<T>(A.g), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_W2)))) return e;
       if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.f, D.h, K, wsp<T>(A.du), wsp<T>(A.xn2), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_W1)))) return e;
-      if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.h, D.h, K, wsp<T>(A.dx1), wsp<T>(A.ctx), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_WO)))) return e;
+      if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.h, D.h, K, wsp<T>(A.dx1d), wsp<T>(A.ctx), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_WO)))) return e;
       if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, 3 * D.h, D.h, K, wsp<T>(A.dqkv), wsp<T>(A.xn1), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_WQKV)))) return e;
     }
     return hipSuccess;
@@ -415,7 +451,7 @@ struct StageOps {
     const T* x = slot(mb);
     for (int l = 0; l < D.L; ++l) {
       T* y = (l == D.L - 1) ? y_out : wsp<T>(S->ws.ping[l & 1]);
-      if ((e = layer_forward(l, x, y, S->ws.fwd, 0, false, false))) return e;
+      if ((e = layer_forward(l, mb, x, y, S->ws.fwd, 0, false, false))) return e;
       x = y;
     }
     return hipSuccess;
@@ -429,7 +465,7 @@ struct StageOps {
     for (int l = 0; l < D.L; ++l) {
       const bool last = (l == D.L - 1);
       T* y = last ? y_out : wsp<T>(S->ws.layer[l].y);
-      if ((e = layer_forward(l, x, y, S->ws.layer[l], rs, true, last && y_out == nullptr))) return e;
+      if ((e = layer_forward(l, mb, x, y, S->ws.layer[l], rs, true, last && y_out == nullptr))) return e;
       x = y;
     }
     return hipSuccess;
@@ -448,7 +484,7 @@ struct StageOps {
     for (int l = D.L - 1; l >= 0; --l) {
       const T* x = (l == 0) ? slot(mb) : wsp<T>(S->ws.layer[l - 1].y);
       T* dx = (l == 0) ? dx_out : wsp<T>(S->ws.layer[l - 1].dy) + (size_t)rs * D.E;
-      if ((e = layer_backward(l, x, dx, S->ws.layer[l], rs))) return e;
+      if ((e = layer_backward(l, mb, x, dx, S->ws.layer[l], rs))) return e;
     }
     if (++S->pending == D.G) {
       if ((e = flush_wgrads(S->pending))) return e;
@@ -645,6 +681,15 @@ varuna_status_t varuna_stage_grad_flush(varuna_stage_t* st, void* hip_stream) {
   return hip_result(e, "varuna_stage_grad_flush");
 }
 
+varuna_status_t varuna_stage_set_dropout_seed(varuna_stage_t* st, uint64_t seed) {
+  if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
+  for (char f : st->forwarded)
+    if (f) return fail(VARUNA_ESTATE, "the dropout seed cannot change between a forward and its backward");
+  st->seed = seed;
+  st->kept_mb = -1;
+  return VARUNA_OK;
+}
+
 varuna_status_t varuna_stage_grad_stats(varuna_stage_t* st, float* out2, void* hip_stream) {
   if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
   if (!out2) return fail(VARUNA_EINVAL, "NULL output pointer");
@@ -808,8 +853,8 @@ varuna_status_t varuna_op_attention_fwd(int32_t dtype, int32_t variant, int32_t 
   if (!qkv || !ctx) return fail(VARUNA_EINVAL, "NULL tensor pointer");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
-  if (dtype == VARUNA_F32) e = AttnDispatch<float>::fwd(variant, static_cast<const float*>(qkv), static_cast<float*>(ctx), lse_f32, b, s, heads, d, causal, st);
-  else if (dtype == VARUNA_BF16) e = AttnDispatch<bf16>::fwd(variant, static_cast<const bf16*>(qkv), static_cast<bf16*>(ctx), lse_f32, b, s, heads, d, causal, st);
+  if (dtype == VARUNA_F32) e = AttnDispatch<float>::fwd(variant, static_cast<const float*>(qkv), static_cast<float*>(ctx), lse_f32, b, s, heads, d, causal, DropArgs{}, st);
+  else if (dtype == VARUNA_BF16) e = AttnDispatch<bf16>::fwd(variant, static_cast<const bf16*>(qkv), static_cast<bf16*>(ctx), lse_f32, b, s, heads, d, causal, DropArgs{}, st);
   else return fail(VARUNA_EINVAL, "unknown dtype %d", dtype);
   return hip_result(e, "varuna_op_attention_fwd");
 }
@@ -822,8 +867,8 @@ varuna_status_t varuna_op_attention_bwd(int32_t dtype, int32_t variant, int32_t 
   if (!qkv || !ctx || !lse_f32 || !dctx || !dqkv || !delta_f32) return fail(VARUNA_EINVAL, "NULL tensor pointer");
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
-  if (dtype == VARUNA_F32) e = AttnDispatch<float>::bwd(variant, static_cast<const float*>(qkv), static_cast<const float*>(ctx), lse_f32, static_cast<const float*>(dctx), static_cast<float*>(dqkv), delta_f32, b, s, heads, d, causal, st);
-  else if (dtype == VARUNA_BF16) e = AttnDispatch<bf16>::bwd(variant, static_cast<const bf16*>(qkv), static_cast<const bf16*>(ctx), lse_f32, static_cast<const bf16*>(dctx), static_cast<bf16*>(dqkv), delta_f32, b, s, heads, d, causal, st);
+  if (dtype == VARUNA_F32) e = AttnDispatch<float>::bwd(variant, static_cast<const float*>(qkv), static_cast<const float*>(ctx), lse_f32, static_cast<const float*>(dctx), static_cast<float*>(dqkv), delta_f32, b, s, heads, d, causal, DropArgs{}, st);
+  else if (dtype == VARUNA_BF16) e = AttnDispatch<bf16>::bwd(variant, static_cast<const bf16*>(qkv), static_cast<const bf16*>(ctx), lse_f32, static_cast<const bf16*>(dctx), static_cast<bf16*>(dqkv), delta_f32, b, s, heads, d, causal, DropArgs{}, st);
   else return fail(VARUNA_EINVAL, "unknown dtype %d", dtype);
   return hip_result(e, "varuna_op_attention_bwd");
 }

@@ -42,6 +42,7 @@ class StageConfig:
     ln_eps: float = 1e-5
     seed: int = 20211104
     wgrad_group: int = 1  # micro-batches per weight-gradient GEMM (library knob, not part of the workload)
+    dropout_p: float = 0.0  # dropout probability (0: none; the paper's configs name none)
 
     @property
     def tokens(self) -> int:

@@ -16,12 +16,14 @@ def oracle_shape(cfg: synth.StageConfig) -> O.StageShape:
                         cfg.mlp_hidden, cfg.causal, cfg.ln_eps)
 
 
-def gpu_stage_step(cfg, params, xs, dys, device="cuda:0", interleave=False, last_stage=False):
+def gpu_stage_step(cfg, params, xs, dys, device="cuda:0", interleave=False, last_stage=False, seed=0):
     """Runs reset, M forwards, M backward_recomputes (last_stage: M times forward_keep
     followed at once by backward_stored). Returns (stage, ys, dxs) with outputs as CPU
     tensors; the accumulated gradients stay in stage.grads."""
     st = B.Stage(cfg, device)
     st.set_params(params)
+    if cfg.dropout_p > 0:
+        st.set_dropout_seed(seed)
     st.grad_accum_reset()
     n = len(xs)
     dx_ = [x.to(device) for x in xs]
@@ -49,10 +51,14 @@ def gpu_stage_step(cfg, params, xs, dys, device="cuda:0", interleave=False, last
     return st, [y.cpu() for y in ys], [d.cpu() for d in dxs]
 
 
-def oracle_stage_step(cfg, params, xs, dys):
+def oracle_stage_step(cfg, params, xs, dys, seed=0):
     sh = oracle_shape(cfg)
     p64 = synth.params_to_f64(params)
-    return O.stage_step([synth.to_f64(x) for x in xs], [synth.to_f64(d) for d in dys], p64, sh)
+    drop = None
+    if cfg.dropout_p > 0:
+        from oracle.dropout_oracle import Dropout
+        drop = Dropout(cfg.dropout_p, seed)
+    return O.stage_step([synth.to_f64(x) for x in xs], [synth.to_f64(d) for d in dys], p64, sh, drop)
 
 
 def compare_step(cfg, st, ys, dxs, ref, tol=None, label=""):

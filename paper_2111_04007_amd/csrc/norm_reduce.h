@@ -122,6 +122,103 @@ __global__ __launch_bounds__(LN_ROWS_PER_BLOCK* kWave) void layernorm_bwd_dx_ker
   }
 }
 
+// Raw 16-byte vectors of a row held in registers (NC per lane), so that every tensor is read
+// from memory once: rows of up to NC * 64 * VEC elements.
+template <typename T, int VEC> struct RawVec { typedef T type __attribute__((ext_vector_type(VEC))); };
+
+template <typename T, int VEC, int NC>
+__global__ __launch_bounds__(LN_ROWS_PER_BLOCK* kWave) void layernorm_fwd_cached_kernel(
+    const T* __restrict__ x, const T* __restrict__ gamma, const T* __restrict__ beta,
+    T* __restrict__ y, float* __restrict__ stats, int64_t rows, int h, float eps) {
+  typedef typename RawVec<T, VEC>::type Raw;
+  const int lane = threadIdx.x % kWave;
+  const int64_t row = (int64_t)blockIdx.x * LN_ROWS_PER_BLOCK + threadIdx.x / kWave;
+  if (row >= rows) return;
+  const T* xr = x + row * h;
+  Raw xc[NC];
+  float s = 0.f;
+#pragma unroll
+  for (int it = 0; it < NC; ++it) {
+    const int j = (it * kWave + lane) * VEC;
+    if (j < h) {
+      xc[it] = *reinterpret_cast<const Raw*>(xr + j);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) s += to_f32(xc[it][i]);
+    }
+  }
+  const float mean = wave_sum(s) / (float)h;
+  s = 0.f;
+#pragma unroll
+  for (int it = 0; it < NC; ++it) {
+    const int j = (it * kWave + lane) * VEC;
+    if (j < h) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) { const float c = to_f32(xc[it][i]) - mean; s += c * c; }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(s) / (float)h + eps);
+  if (stats && lane == 0) { stats[row] = mean; stats[rows + row] = rstd; }
+  T* yr = y + row * h;
+#pragma unroll
+  for (int it = 0; it < NC; ++it) {
+    const int j = (it * kWave + lane) * VEC;
+    if (j < h) {
+      const Raw g = *reinterpret_cast<const Raw*>(gamma + j), b = *reinterpret_cast<const Raw*>(beta + j);
+      Raw o;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) o[i] = from_f32<T>(to_f32(g[i]) * ((to_f32(xc[it][i]) - mean) * rstd) + to_f32(b[i]));
+      *reinterpret_cast<Raw*>(yr + j) = o;
+    }
+  }
+}
+
+template <typename T, int VEC, int NC>
+__global__ __launch_bounds__(LN_ROWS_PER_BLOCK* kWave) void layernorm_bwd_dx_cached_kernel(
+    const T* __restrict__ dy, const T* __restrict__ x, const float* __restrict__ stats,
+    const T* __restrict__ gamma, const T* __restrict__ res, T* __restrict__ dx, int64_t rows, int h) {
+  typedef typename RawVec<T, VEC>::type Raw;
+  const int lane = threadIdx.x % kWave;
+  const int64_t row = (int64_t)blockIdx.x * LN_ROWS_PER_BLOCK + threadIdx.x / kWave;
+  if (row >= rows) return;
+  const float mean = stats[row], rstd = stats[rows + row];
+  const T* xr = x + row * h;
+  const T* dyr = dy + row * h;
+  Raw xc[NC], dc[NC];   // the row of x and of dy; gamma is re-read (it stays in cache)
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int it = 0; it < NC; ++it) {
+    const int j = (it * kWave + lane) * VEC;
+    if (j < h) {
+      xc[it] = *reinterpret_cast<const Raw*>(xr + j);
+      dc[it] = *reinterpret_cast<const Raw*>(dyr + j);
+      const Raw g = *reinterpret_cast<const Raw*>(gamma + j);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) {
+        const float dxh = to_f32(dc[it][i]) * to_f32(g[i]);
+        s1 += dxh;
+        s2 += dxh * ((to_f32(xc[it][i]) - mean) * rstd);
+      }
+    }
+  }
+  const float m1 = wave_sum(s1) / (float)h, m2 = wave_sum(s2) / (float)h;
+  const T* rr = res + row * h;
+  T* dxr = dx + row * h;
+#pragma unroll
+  for (int it = 0; it < NC; ++it) {
+    const int j = (it * kWave + lane) * VEC;
+    if (j < h) {
+      const Raw g = *reinterpret_cast<const Raw*>(gamma + j), r = *reinterpret_cast<const Raw*>(rr + j);
+      Raw o;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) {
+        const float xh = (to_f32(xc[it][i]) - mean) * rstd;
+        o[i] = from_f32<T>(to_f32(r[i]) + rstd * (to_f32(dc[it][i]) * to_f32(g[i]) - m1 - xh * m2));
+      }
+      *reinterpret_cast<Raw*>(dxr + j) = o;
+    }
+  }
+}
+
 // Stage 1 of a column reduction over rows [chunk*CR_CHUNK, +CR_CHUNK).
 // LNMODE 0: partial[chunk][c] = sum_t a[t,c].
 // LNMODE 1: partial[chunk][c] = sum_t a[t,c]*xhat[t,c] (dgamma) and
@@ -189,11 +286,77 @@ template <typename T>
 inline hipError_t launch_layernorm_fwd(const T* x, const T* gamma, const T* beta, T* y, float* stats,
                                        int64_t rows, int h, float eps, hipStream_t st) {
   dim3 grid((unsigned)((rows + LN_ROWS_PER_BLOCK - 1) / LN_ROWS_PER_BLOCK)), block(LN_ROWS_PER_BLOCK * kWave);
-  if (h % ln_vec<T>() == 0 && ln_aligned16({x, gamma, beta, y}))
-    hipLaunchKernelGGL((layernorm_fwd_kernel<T, ln_vec<T>()>), grid, block, 0, st, x, gamma, beta, y, stats, rows, h, eps);
-  else
+  constexpr int V = ln_vec<T>();
+  if (h % V == 0 && ln_aligned16({x, gamma, beta, y})) {
+    const int nv = (h / V + kWave - 1) / kWave;  // 16-byte vectors per lane
+    if (nv <= 4) hipLaunchKernelGGL((layernorm_fwd_cached_kernel<T, V, 4>), grid, block, 0, st, x, gamma, beta, y, stats, rows, h, eps);
+    else if (nv <= 8) hipLaunchKernelGGL((layernorm_fwd_cached_kernel<T, V, 8>), grid, block, 0, st, x, gamma, beta, y, stats, rows, h, eps);
+    else if (nv <= 16) hipLaunchKernelGGL((layernorm_fwd_cached_kernel<T, V, 16>), grid, block, 0, st, x, gamma, beta, y, stats, rows, h, eps);
+    else hipLaunchKernelGGL((layernorm_fwd_kernel<T, V>), grid, block, 0, st, x, gamma, beta, y, stats, rows, h, eps);
+  } else
     hipLaunchKernelGGL((layernorm_fwd_kernel<T, 1>), grid, block, 0, st, x, gamma, beta, y, stats, rows, h, eps);
   return hipGetLastError();
+}
+
+// The same partial column sums with 16-byte accesses: 32 column groups of VEC columns x 8
+// row lanes per block; a wavefront reads two 512-byte row segments per instruction.
+template <typename T, int LNMODE, int VEC>
+__global__ __launch_bounds__(256) void colreduce_partial_vec_kernel(
+    const T* __restrict__ a, const T* __restrict__ x, const float* __restrict__ stats,
+    float* __restrict__ partial, int64_t rows, int64_t n) {
+  constexpr int CG = 32, RL = 8;
+  __shared__ float sh[2][RL][CG * VEC];
+  const int cg = threadIdx.x % CG, rl = threadIdx.x / CG;
+  const int64_t col = ((int64_t)blockIdx.x * CG + cg) * VEC;
+  const int64_t r0 = (int64_t)blockIdx.y * CR_CHUNK;
+  const int64_t r1 = (r0 + CR_CHUNK < rows) ? r0 + CR_CHUNK : rows;
+  float s0[VEC], s1[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
+  if (col < n) {
+    for (int64_t t = r0 + rl; t < r1; t += RL) {
+      float v[VEC];
+      VecLoad<T, VEC>::load(a + t * n + col, v);
+      if (LNMODE) {
+        float xv[VEC];
+        VecLoad<T, VEC>::load(x + t * n + col, xv);
+        const float mu = stats[t], rs = stats[rows + t];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { s0[i] += v[i] * ((xv[i] - mu) * rs); s1[i] += v[i]; }
+      } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) s0[i] += v[i];
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) { sh[0][rl][cg * VEC + i] = s0[i]; if (LNMODE) sh[1][rl][cg * VEC + i] = s1[i]; }
+  __syncthreads();
+  const int64_t width = LNMODE ? 2 * n : n;
+  for (int c = threadIdx.x; c < CG * VEC; c += 256) {
+    const int64_t gc = (int64_t)blockIdx.x * CG * VEC + c;
+    if (gc >= n) continue;
+    float t0 = 0.f, t1 = 0.f;
+#pragma unroll
+    for (int i = 0; i < RL; ++i) { t0 += sh[0][i][c]; if (LNMODE) t1 += sh[1][i][c]; }
+    partial[(int64_t)blockIdx.y * width + gc] = t0;
+    if (LNMODE) partial[(int64_t)blockIdx.y * width + n + gc] = t1;
+  }
+}
+
+template <typename T, int LNMODE>
+inline void launch_colreduce_partial(const T* a, const T* x, const float* stats, float* partial, int64_t rows, int64_t n,
+                                     hipStream_t st) {
+  const int nch = (int)((rows + CR_CHUNK - 1) / CR_CHUNK);
+  constexpr int VEC = 16 / sizeof(T);
+  const bool aligned = (reinterpret_cast<uintptr_t>(a) % 16 == 0) && (x == nullptr || reinterpret_cast<uintptr_t>(x) % 16 == 0);
+  if (n % VEC == 0 && aligned) {
+    dim3 g((unsigned)((n + 32 * VEC - 1) / (32 * VEC)), (unsigned)nch);
+    hipLaunchKernelGGL((colreduce_partial_vec_kernel<T, LNMODE, VEC>), g, dim3(256), 0, st, a, x, stats, partial, rows, n);
+  } else {
+    dim3 g((unsigned)((n + CR_COLS - 1) / CR_COLS), (unsigned)nch);
+    hipLaunchKernelGGL((colreduce_partial_kernel<T, LNMODE>), g, dim3(CR_COLS * CR_ROWLANES), 0, st, a, x, stats, partial, rows, n);
+  }
 }
 
 inline int colreduce_chunks(int64_t rows) { return (int)((rows + CR_CHUNK - 1) / CR_CHUNK); }
@@ -204,13 +367,17 @@ inline hipError_t launch_layernorm_bwd(const T* dy, const T* x, const float* sta
                                        const T* res, T* dx, float* dgamma, float* dbeta,
                                        float* partial, int64_t rows, int h, hipStream_t st) {
   dim3 grid((unsigned)((rows + LN_ROWS_PER_BLOCK - 1) / LN_ROWS_PER_BLOCK)), block(LN_ROWS_PER_BLOCK * kWave);
-  if (h % ln_vec<T>() == 0 && ln_aligned16({dy, x, gamma, res, dx}))
-    hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, ln_vec<T>()>), grid, block, 0, st, dy, x, stats, gamma, res, dx, rows, h);
-  else
+  constexpr int V = ln_vec<T>();
+  if (h % V == 0 && ln_aligned16({dy, x, gamma, res, dx})) {
+    const int nv = (h / V + kWave - 1) / kWave;
+    if (nv <= 4) hipLaunchKernelGGL((layernorm_bwd_dx_cached_kernel<T, V, 4>), grid, block, 0, st, dy, x, stats, gamma, res, dx, rows, h);
+    else if (nv <= 8) hipLaunchKernelGGL((layernorm_bwd_dx_cached_kernel<T, V, 8>), grid, block, 0, st, dy, x, stats, gamma, res, dx, rows, h);
+    else if (nv <= 16) hipLaunchKernelGGL((layernorm_bwd_dx_cached_kernel<T, V, 16>), grid, block, 0, st, dy, x, stats, gamma, res, dx, rows, h);
+    else hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, V>), grid, block, 0, st, dy, x, stats, gamma, res, dx, rows, h);
+  } else
     hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, 1>), grid, block, 0, st, dy, x, stats, gamma, res, dx, rows, h);
   const int nch = colreduce_chunks(rows);
-  dim3 g2((unsigned)((h + CR_COLS - 1) / CR_COLS), (unsigned)nch);
-  hipLaunchKernelGGL((colreduce_partial_kernel<T, 1>), g2, dim3(CR_COLS * CR_ROWLANES), 0, st, dy, x, stats, partial, rows, (int64_t)h);
+  launch_colreduce_partial<T, 1>(dy, x, stats, partial, rows, (int64_t)h, st);
   hipLaunchKernelGGL(colreduce_final_kernel, dim3((unsigned)((h + 255) / 256)), dim3(256), 0, st, partial, nch, (int64_t)h, dgamma, dbeta);
   return hipGetLastError();
 }
@@ -218,8 +385,7 @@ inline hipError_t launch_layernorm_bwd(const T* dy, const T* x, const float* sta
 template <typename T>
 inline hipError_t launch_colsum(const T* a, float* out, float* partial, int64_t rows, int64_t n, hipStream_t st) {
   const int nch = colreduce_chunks(rows);
-  dim3 g2((unsigned)((n + CR_COLS - 1) / CR_COLS), (unsigned)nch);
-  hipLaunchKernelGGL((colreduce_partial_kernel<T, 0>), g2, dim3(CR_COLS * CR_ROWLANES), 0, st, a, (const T*)nullptr, (const float*)nullptr, partial, rows, n);
+  launch_colreduce_partial<T, 0>(a, (const T*)nullptr, (const float*)nullptr, partial, rows, n, st);
   hipLaunchKernelGGL(colreduce_final_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, partial, nch, n, out, (float*)nullptr);
   return hipGetLastError();
 }

@@ -182,17 +182,25 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
   const int tile_n = (logical % width) / gsize;
   const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
 
-  // With two waves per SIMD only the upper half of the waves (one per SIMD) issues the
-  // direct loads: a load instruction holds its wave at issue until the texture addresser
-  // takes it (about 16 cycles per 1 KB, 64 per k-tile and CU), and while one wave of a SIMD
-  // is held there the other keeps the matrix pipe fed.
-  constexpr int NI = (NW == 8) ? 4 : NW;
+  // A direct load holds its wave at issue until the texture addresser takes it (about 20
+  // cycles per 1 KB load, 64 loads per k-tile and CU), and a wave held there issues no
+  // products.  With two waves per SIMD the loads are therefore arranged so that while one
+  // wave of a SIMD is held at issue the other keeps the matrix pipe fed (measured per kernel):
+  //   both operands k-major: only the upper half of the waves (one per SIMD) sends loads,
+  //     the whole k-tile right after the barrier that frees the stage;
+  //   an m/n-major operand: every wave sends its share, the lower half right after that
+  //     barrier, the upper half one k-step later.
+  // With one wave per SIMD every wave sends its share right after the barrier.
+  constexpr bool HAND = !(A_KMAJOR && B_KMAJOR);
+  constexpr bool SPLIT = (NW == 8) && HAND;          // two issue points
+  constexpr int NI = (NW == 8 && !HAND) ? 4 : NW;    // number of issuing waves
   const bool issuer = wave >= NW - NI;
-  const int iw = issuer ? wave - (NW - NI) : 0;
+  const int iw = wave - (NW - NI);
+  const bool early = !SPLIT || wave < NW / 2;
   DgLoader<BM, NI, A_KMAJOR> la;
   DgLoader<BN, NI, B_KMAJOR> lb;
-  la.init(a, lda, m0, iw, lane, (uint32_t)((A_KMAJOR ? (int64_t)tiles_m * BM : (int64_t)K) * lda * 2));
-  lb.init(b, ldb, n0, iw, lane, (uint32_t)((B_KMAJOR ? (int64_t)tiles_n * BN : (int64_t)K) * ldb * 2));
+  la.init(a, lda, m0, issuer ? iw : 0, lane, (uint32_t)((A_KMAJOR ? (int64_t)tiles_m * BM : (int64_t)K) * lda * 2));
+  lb.init(b, ldb, n0, issuer ? iw : 0, lane, (uint32_t)((B_KMAJOR ? (int64_t)tiles_n * BN : (int64_t)K) * ldb * 2));
   constexpr int LPT = DgLoader<BM, NI, A_KMAJOR>::LPT + DgLoader<BN, NI, B_KMAJOR>::LPT;
 
   floatx16 acc[TM][TN];
@@ -217,7 +225,6 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
   }
   __builtin_amdgcn_s_barrier();
 
-  constexpr bool HAND = !(A_KMAJOR && B_KMAJOR);
   DgFragReg<A_KMAJOR, HAND> fa[2][TM];
   DgFragReg<B_KMAJOR, HAND> fb[2][TN];
 #pragma unroll
@@ -268,11 +275,15 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
     bf16* cur = smem + (kt & 1) * STAGE_ELEMS;
     bf16* nxt = smem + ((kt & 1) ^ 1) * STAGE_ELEMS;
     kstep(S0{}, cur, 1);
+    if (SPLIT && !early && kt >= 1 && kt + 1 < nk) {  // the late half's share of tile kt+1 (tiles 0, 1: sent above)
+      la.issue(nxt, kt + 1, iw);
+      lb.issue(nxt + BM * DG_BK, kt + 1, iw);
+    }
     kstep(S1{}, cur, 2);
     kstep(S0{}, cur, 3);
     __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
     __builtin_amdgcn_s_barrier();
-    if (issuer && kt + 2 < nk) {
+    if (issuer && early && kt + 2 < nk) {
       la.issue(cur, kt + 2, iw);
       lb.issue(cur + BM * DG_BK, kt + 2, iw);
     }

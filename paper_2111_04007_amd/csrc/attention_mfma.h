@@ -82,6 +82,16 @@ __device__ __forceinline__ bf16x8 at_tr_frag(const bf16* tile, int r0, int col_b
   return u.v;
 }
 
+// acc += A B with the accumulator pinned to the accumulation registers.  With one wave per
+// SIMD the dK/dV kernel spreads over both halves of the register file, and left to itself the
+// compiler keeps these long-lived accumulators in the ordinary half and copies all 16
+// registers across around every product.  The product is opaque to the compiler here, so the
+// wait states a later read of the result needs are inserted by hand (at_mfma_settle).
+__device__ __forceinline__ void at_mfma_acc(floatx16& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void at_mfma_settle() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+
 __device__ __forceinline__ bf16x8 at_pack8(const float* p) {
   bf16x8 r;
 #pragma unroll
@@ -140,10 +150,23 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
     for (int sb = 0; sb < 2; ++sb) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) sc[sb][r] = 0.f;
+      // fragments fetched as one batch ahead of their products (see the dK/dV kernel)
+      bf16x8 kfr[C::KD];
+#pragma unroll
+      for (int t = 0; t < C::KD; ++t) kfr[t] = at_row_frag<D>(sk, sb * 32, 16 * t, lane);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int t = 0; t < C::KD; ++t)
-        sc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_row_frag<D>(sk, sb * 32, 16 * t, lane), qf[t], sc[sb], 0, 0, 0);
+        sc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[t], qf[t], sc[sb], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    // V^T fragments of the first 32 keys: in flight during the softmax arithmetic
+    bf16x8 vtr[2][C::DB];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int db = 0; db < C::DB; ++db) vtr[t][db] = at_tr_frag<D>(sv, 16 * t, db * 32, lane);
+    __builtin_amdgcn_sched_barrier(0);
     float p[2][16];
     float mx = -INFINITY;
     const bool need_mask = CAUSAL && (k0 + 63 > qw);
@@ -190,15 +213,25 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
     for (int i = 0; i < C::DB; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int sb = 0; sb < 2; ++sb)
+    for (int sb = 0; sb < 2; ++sb) {
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const bf16x8 pf = at_pack8(&p[sb][8 * t]);
 #pragma unroll
         for (int db = 0; db < C::DB; ++db)
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_tr_frag<D>(sv, sb * 32 + 16 * t, db * 32, lane), pf, o[db], 0, 0, 0);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vtr[t][db], pf, o[db], 0, 0, 0);
       }
+      __builtin_amdgcn_sched_barrier(0);
+      if (sb == 0) {  // the second 32 keys' fragments, into the same registers
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int db = 0; db < C::DB; ++db) vtr[t][db] = at_tr_frag<D>(sv, 32 + 16 * t, db * 32, lane);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
   }
   l += __shfl_xor(l, 32, 64);
   const float inv = (DROP ? drop.scale : 1.0f) / l;
@@ -272,18 +305,39 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
       rv.load(base + (int64_t)(kb + 1) * 64 * ld + 2 * h, ld, tid);
     }
     const int k0 = kb * 64;
-    if (CAUSAL && k0 > qw + 31) continue;
+    // (no per-wave skip of key blocks in this wave's future: the mask zeroes them, and a
+    // branch around the products costs registers)
     const bool need_mask = CAUSAL && (k0 + 63 > qw);
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) {
       floatx16 sc, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+      // fragments fetched in batches ahead of their products (see the dK/dV kernel)
+      constexpr int KH = (C::KD + 1) / 2;
 #pragma unroll
-      for (int t = 0; t < C::KD; ++t) {
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_row_frag<D>(sk, sb * 32, 16 * t, lane), qf[t], sc, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_row_frag<D>(sv, sb * 32, 16 * t, lane), gf[t], dp, 0, 0, 0);
+      for (int t0 = 0; t0 < C::KD; t0 += KH) {
+        bf16x8 kfr[KH], vfr[KH];
+#pragma unroll
+        for (int t = 0; t < KH; ++t)
+          if (t0 + t < C::KD) {
+            kfr[t] = at_row_frag<D>(sk, sb * 32, 16 * (t0 + t), lane);
+            vfr[t] = at_row_frag<D>(sv, sb * 32, 16 * (t0 + t), lane);
+          }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < KH; ++t)
+          if (t0 + t < C::KD) {
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[t], qf[t0 + t], sc, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[t], gf[t0 + t], dp, 0, 0, 0);
+          }
+        __builtin_amdgcn_sched_barrier(0);
       }
+      // K^T fragments of the last product: in flight during the arithmetic below
+      bf16x8 ktr[2][C::DB];
+#pragma unroll
+      for (int db = 0; db < C::DB; ++db) ktr[0][db] = at_tr_frag<D>(sk, sb * 32, db * 32, lane);
+      __builtin_amdgcn_sched_barrier(0);
       if (DROP) {  // dP = dropout'(dO V^T): same mask words as the forward kernel
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -302,12 +356,17 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
         }
         ds[r] = pr * (dp[r] - dl);
       }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int db = 0; db < C::DB; ++db) ktr[1][db] = at_tr_frag<D>(sk, sb * 32 + 16, db * 32, lane);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const bf16x8 df = at_pack8(&ds[8 * t]);
 #pragma unroll
         for (int db = 0; db < C::DB; ++db)
-          dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_tr_frag<D>(sk, sb * 32 + 16 * t, db * 32, lane), df, dq[db], 0, 0, 0);
+          dq[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktr[t][db], df, dq[db], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
@@ -384,18 +443,47 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
       load_stat(qb + 1);
     }
     const int q0 = qb * 64;
-    if (CAUSAL && q0 + 63 < kw) continue;  // every query of the block precedes this wave's keys
+    // (A wave whose keys all follow the tile's queries is not skipped: that happens in a
+    // workgroup's first tile only, the mask zeroes its contribution, and a branch around the
+    // products makes the compiler copy all accumulators.)
     const bool need_mask = CAUSAL && (q0 < kw + 31);
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) {
+      // The LDS fragments of each group of products are fetched as one batch ahead of the
+      // products (the scheduling fences keep it that way: left alone, the compiler pairs
+      // every read with its product and waits for each one, which exposes the LDS latency
+      // once per product with one wave per SIMD).
       floatx16 sc, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+      constexpr int KH = (C::KD + 1) / 2;  // k-steps per batch (two batches bound the registers held by fragments)
 #pragma unroll
-      for (int t = 0; t < C::KD; ++t) {
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_row_frag<D>(sq, sb * 32, 16 * t, lane), kf[t], sc, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_row_frag<D>(sg, sb * 32, 16 * t, lane), vf[t], dp, 0, 0, 0);
+      for (int t0 = 0; t0 < C::KD; t0 += KH) {
+        bf16x8 qfr[KH], gfr[KH];
+#pragma unroll
+        for (int t = 0; t < KH; ++t)
+          if (t0 + t < C::KD) {
+            qfr[t] = at_row_frag<D>(sq, sb * 32, 16 * (t0 + t), lane);
+            gfr[t] = at_row_frag<D>(sg, sb * 32, 16 * (t0 + t), lane);
+          }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < KH; ++t)
+          if (t0 + t < C::KD) {
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr[t], kf[t0 + t], sc, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gfr[t], vf[t0 + t], dp, 0, 0, 0);
+          }
+        __builtin_amdgcn_sched_barrier(0);
       }
+      // transposed dO / Q fragments of the second pair of products, first half: in flight
+      // during the softmax arithmetic
+      bf16x8 gtr[2][C::DB], qtr[2][C::DB];
+#pragma unroll
+      for (int db = 0; db < C::DB; ++db) {
+        gtr[0][db] = at_tr_frag<D>(sg, sb * 32, db * 32, lane);
+        qtr[0][db] = at_tr_frag<D>(sq, sb * 32, db * 32, lane);
+      }
+      __builtin_amdgcn_sched_barrier(0);
       float pr[16], ds[16];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -416,18 +504,28 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
           ds[r] = p * (dp[r] * f - d4[e]);
         }
       }
+      __builtin_amdgcn_sched_barrier(0);
+      // second half of the fragments: in flight during the first half's products
+#pragma unroll
+      for (int db = 0; db < C::DB; ++db) {
+        gtr[1][db] = at_tr_frag<D>(sg, sb * 32 + 16, db * 32, lane);
+        qtr[1][db] = at_tr_frag<D>(sq, sb * 32 + 16, db * 32, lane);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const bf16x8 pf = at_pack8(&pr[8 * t]);
         const bf16x8 df = at_pack8(&ds[8 * t]);
 #pragma unroll
         for (int db = 0; db < C::DB; ++db) {
-          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_tr_frag<D>(sg, sb * 32 + 16 * t, db * 32, lane), pf, dv[db], 0, 0, 0);
-          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_tr_frag<D>(sq, sb * 32 + 16 * t, db * 32, lane), df, dk[db], 0, 0, 0);
+          at_mfma_acc(dv[db], gtr[t][db], pf);
+          at_mfma_acc(dk[db], qtr[t][db], df);
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
+  at_mfma_settle();
   bf16* krow = dqkv + ((int64_t)bi * s + key) * ld + h + head * D;
   bf16* vrow = krow + h;
 #pragma unroll

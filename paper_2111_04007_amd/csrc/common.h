@@ -100,7 +100,8 @@ enum EpiMode : int {
   EPI_BIAS_RES = 2,   // out = acc + bias[n] + aux_in[m,n]
   EPI_DGELU = 3,      // out = acc * GeLU'(aux_in[m,n])
   EPI_PLAIN = 4,      // out = acc
-  EPI_ACCUM_F32 = 5   // out_f32[m,n] += acc
+  EPI_ACCUM_F32 = 5,  // out_f32[m,n] += acc
+  EPI_STORE_F32 = 6   // out_f32[split][m,n] = acc over this split's share of the reduction (split-K partial sums)
 };
 
 template <typename T>
@@ -112,6 +113,7 @@ struct EpiArgs {
   float* out_f32;    // [M,N] accumulator for EPI_ACCUM_F32
   int64_t ldc;       // row pitch of out / aux_in / aux_out / out_f32 in elements
   DropArgs drop;     // EPI_BIAS_RES only: out = aux_in + dropout(acc + bias)
+  int64_t split_stride;  // EPI_STORE_F32: elements between the partial results of consecutive splits
 };
 
 // One output element.

@@ -211,13 +211,15 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = K / DG_BK;
+  // gridDim.y splits of the reduction (EPI_STORE_F32 only): this workgroup owns k-tiles kt0 .. kt0+nk-1
+  const int nk = K / DG_BK / (int)gridDim.y;
+  const int kt0 = (int)blockIdx.y * nk;
   if (issuer) {
-    la.issue(smem, 0, iw);
-    lb.issue(smem + BM * DG_BK, 0, iw);
+    la.issue(smem, kt0, iw);
+    lb.issue(smem + BM * DG_BK, kt0, iw);
     if (nk > 1) {
-      la.issue(smem + STAGE_ELEMS, 1, iw);
-      lb.issue(smem + STAGE_ELEMS + BM * DG_BK, 1, iw);
+      la.issue(smem + STAGE_ELEMS, kt0 + 1, iw);
+      lb.issue(smem + STAGE_ELEMS + BM * DG_BK, kt0 + 1, iw);
       __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LPT));  // tile 0 landed, tile 1 may be in flight
     } else {
       __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(0));
@@ -276,22 +278,22 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
     bf16* nxt = smem + ((kt & 1) ^ 1) * STAGE_ELEMS;
     kstep(S0{}, cur, 1);
     if (SPLIT && !early && kt >= 1 && kt + 1 < nk) {  // the late half's share of tile kt+1 (tiles 0, 1: sent above)
-      la.issue(nxt, kt + 1, iw);
-      lb.issue(nxt + BM * DG_BK, kt + 1, iw);
+      la.issue(nxt, kt0 + kt + 1, iw);
+      lb.issue(nxt + BM * DG_BK, kt0 + kt + 1, iw);
     }
     kstep(S1{}, cur, 2);
     kstep(S0{}, cur, 3);
     __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
     __builtin_amdgcn_s_barrier();
     if (issuer && early && kt + 2 < nk) {
-      la.issue(cur, kt + 2, iw);
-      lb.issue(cur + BM * DG_BK, kt + 2, iw);
+      la.issue(cur, kt0 + kt + 2, iw);
+      lb.issue(cur + BM * DG_BK, kt0 + kt + 2, iw);
     }
     kstep(S1{}, nxt, 0);
   }
 
   const int frow = lane & 31, fchunk = lane >> 5;
-  if constexpr (MODE == EPI_ACCUM_F32) {
+  if constexpr (MODE == EPI_ACCUM_F32 || MODE == EPI_STORE_F32) {
     // out_f32 += acc.  Reading the old values through registers would leave only a few KB
     // in flight per CU (the accumulators own the register file), so the old tile is
     // streamed into the now idle LDS with the same direct loads as the operands: each wave
@@ -305,7 +307,8 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
     __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
     __builtin_amdgcn_s_barrier();               // every wave is done with the operand stages
     unsigned char* mybuf = dg_smem + wave * (2 * PASS_BYTES);
-    float* cbase = epi.out_f32 + (m0 + wm * WM) * epi.ldc + n0 + wn * WN;
+    float* cbase = epi.out_f32 + (MODE == EPI_STORE_F32 ? (int64_t)blockIdx.y * epi.split_stride : 0) +
+                   (m0 + wm * WM) * epi.ldc + n0 + wn * WN;
     auto issue_pass = [&](int pass) {
       unsigned char* buf = mybuf + (pass & 1) * PASS_BYTES;
 #pragma unroll
@@ -316,11 +319,15 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
                                          (lds_ptr_t)(buf + q * 1024), 16, 0, 0);
       }
     };
-    issue_pass(0);
-    if (TM > 1) issue_pass(1);
+    if constexpr (MODE == EPI_ACCUM_F32) {
+      issue_pass(0);
+      if (TM > 1) issue_pass(1);
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      if (i + 1 < TM) __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(NINS)); else __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(0));
+      if constexpr (MODE == EPI_ACCUM_F32) {
+        if (i + 1 < TM) __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(NINS)); else __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(0));
+      }
       const unsigned char* buf = mybuf + (i & 1) * PASS_BYTES;
       float* crow = cbase + (int64_t)(i * 32 + frow) * epi.ldc;
 #pragma unroll
@@ -328,12 +335,14 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int c = j * 8 + g * 2 + fchunk;
-          floatx4 v = *reinterpret_cast<const floatx4*>(buf + frow * (WN * 4) + ((c ^ (frow & 15)) << 4));
+          floatx4 v = {0.f, 0.f, 0.f, 0.f};   // EPI_STORE_F32: a partial sum of its own, nothing to add to
+          if constexpr (MODE == EPI_ACCUM_F32)
+            v = *reinterpret_cast<const floatx4*>(buf + frow * (WN * 4) + ((c ^ (frow & 15)) << 4));
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] += acc[i][j][g * 4 + e];
           *reinterpret_cast<floatx4*>(crow + c * 4) = v;
         }
-      if (i + 2 < TM) {
+      if (MODE == EPI_ACCUM_F32 && i + 2 < TM) {
         __builtin_amdgcn_s_waitcnt(DG_WAIT_LGKM0);  // this buffer's LDS reads are done before it is refilled
         issue_pass(i + 2);
       }
@@ -414,7 +423,7 @@ inline int dg_choose_variant(int64_t M, int64_t N, int64_t K, int64_t lda, int64
 
 template <int BM, int BN, int WGM, int WGN, bool AK, bool BK_, int MODE>
 inline hipError_t dg_launch_one(const bf16* a, int64_t lda, const bf16* b, int64_t ldb, int64_t M, int64_t N,
-                                int64_t K, const EpiArgs<bf16>& epi, hipStream_t st) {
+                                int64_t K, const EpiArgs<bf16>& epi, int splits, hipStream_t st) {
   auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, AK, BK_, MODE>;
   constexpr size_t smem = (size_t)DG_STAGES * (BM + BN) * DG_BK * sizeof(bf16);
   static bool attr_set = false;
@@ -433,36 +442,74 @@ inline hipError_t dg_launch_one(const bf16* a, int64_t lda, const bf16* b, int64
     group = e2 ? atoi(e2) : 8;
     if (group < 1) group = 1;
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)(tm * tn)), dim3(WGM * WGN * kWave), smem, st, a, lda, b, ldb,
+  if (splits < 1 || (MODE != EPI_STORE_F32 && splits != 1) || (K / DG_BK) % splits != 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(kern, dim3((unsigned)(tm * tn), (unsigned)splits), dim3(WGM * WGN * kWave), smem, st, a, lda, b, ldb,
                      (int)K, tm, tn, epi, xcd_remap, group);
   return hipGetLastError();
 }
 
 template <bool AK, bool BK_, int MODE>
 inline hipError_t dg_launch_variant(int variant, const bf16* a, int64_t lda, const bf16* b, int64_t ldb,
-                                    int64_t M, int64_t N, int64_t K, const EpiArgs<bf16>& epi, hipStream_t st) {
+                                    int64_t M, int64_t N, int64_t K, const EpiArgs<bf16>& epi, int splits, hipStream_t st) {
   switch (variant) {
-    case 5: return dg_launch_one<256, 256, 2, 4, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, st);
-    case 6: return dg_launch_one<256, 256, 2, 2, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, st);
-    case 7: return dg_launch_one<128, 128, 2, 2, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, st);
-    case 8: return dg_launch_one<256, 128, 2, 2, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, st);
+    case 5: return dg_launch_one<256, 256, 2, 4, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 6: return dg_launch_one<256, 256, 2, 2, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 7: return dg_launch_one<128, 128, 2, 2, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 8: return dg_launch_one<256, 128, 2, 2, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, splits, st);
     default: return hipErrorInvalidValue;
   }
 }
 
+// Split-K for weight-gradient GEMMs whose output has too few tiles to fill the chip: the
+// reduction is cut into `splits` equal parts, each workgroup row of the grid writes its
+// partial tile (EPI_STORE_F32) and splitk_reduce adds the partials to the accumulator in a
+// fixed order, so the result stays run-to-run deterministic.  Returns 1 when no split pays.
+inline int dg_wgrad_splits(int64_t M, int64_t N, int64_t K) {
+  const int v = dg_choose_variant(M, N, K, M, N);
+  MgTile t;
+  if (v == 0 || !dg_variant_tile(v, &t)) return 1;
+  const int64_t tiles = (M / t.bm) * (N / t.bn), slots = (v == 5) ? 256 : 512, nk = K / DG_BK;
+  int64_t s = slots / tiles;
+  if (s > 8) s = 8;
+  while (s > 1 && (nk % s != 0 || nk / s < 8)) --s;
+  return (int)(s < 1 ? 1 : s);
+}
+
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits, int64_t n,
+                                                            float* __restrict__ out) {
+  const int64_t n4 = n / 4;  // n is a multiple of 4 (tile sizes)
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x) {
+    floatx4 acc = reinterpret_cast<floatx4*>(out)[i];
+    for (int s = 0; s < splits; ++s) {
+      const floatx4 p = reinterpret_cast<const floatx4*>(partial + (int64_t)s * n)[i];
+      acc[0] += p[0]; acc[1] += p[1]; acc[2] += p[2]; acc[3] += p[3];
+    }
+    reinterpret_cast<floatx4*>(out)[i] = acc;
+  }
+}
+
+inline hipError_t launch_splitk_reduce(const float* partial, int splits, int64_t n, float* out, hipStream_t st) {
+  int64_t nblk = (n / 4 + 255) / 256;
+  if (nblk > 8192) nblk = 8192;
+  if (nblk < 1) nblk = 1;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)nblk), dim3(256), 0, st, partial, splits, n, out);
+  return hipGetLastError();
+}
+
 inline hipError_t launch_gemm_dma(int op, int mode, int variant, const bf16* a, int64_t lda, const bf16* b,
                                   int64_t ldb, int64_t M, int64_t N, int64_t K, const EpiArgs<bf16>& epi,
-                                  hipStream_t st) {
+                                  hipStream_t st, int splits = 1) {
   if (op == GEMM_FWD) {
-    if (mode == EPI_BIAS) return dg_launch_variant<true, true, EPI_BIAS>(variant, a, lda, b, ldb, M, N, K, epi, st);
-    if (mode == EPI_BIAS_GELU) return dg_launch_variant<true, true, EPI_BIAS_GELU>(variant, a, lda, b, ldb, M, N, K, epi, st);
-    if (mode == EPI_BIAS_RES) return dg_launch_variant<true, true, EPI_BIAS_RES>(variant, a, lda, b, ldb, M, N, K, epi, st);
+    if (mode == EPI_BIAS) return dg_launch_variant<true, true, EPI_BIAS>(variant, a, lda, b, ldb, M, N, K, epi, splits, st);
+    if (mode == EPI_BIAS_GELU) return dg_launch_variant<true, true, EPI_BIAS_GELU>(variant, a, lda, b, ldb, M, N, K, epi, splits, st);
+    if (mode == EPI_BIAS_RES) return dg_launch_variant<true, true, EPI_BIAS_RES>(variant, a, lda, b, ldb, M, N, K, epi, splits, st);
   } else if (op == GEMM_DGRAD) {
-    if (mode == EPI_PLAIN) return dg_launch_variant<true, false, EPI_PLAIN>(variant, a, lda, b, ldb, M, N, K, epi, st);
-    if (mode == EPI_DGELU) return dg_launch_variant<true, false, EPI_DGELU>(variant, a, lda, b, ldb, M, N, K, epi, st);
+    if (mode == EPI_PLAIN) return dg_launch_variant<true, false, EPI_PLAIN>(variant, a, lda, b, ldb, M, N, K, epi, splits, st);
+    if (mode == EPI_DGELU) return dg_launch_variant<true, false, EPI_DGELU>(variant, a, lda, b, ldb, M, N, K, epi, splits, st);
   } else if (op == GEMM_WGRAD) {
-    if (mode == EPI_ACCUM_F32) return dg_launch_variant<false, false, EPI_ACCUM_F32>(variant, a, lda, b, ldb, M, N, K, epi, st);
-    if (mode == EPI_PLAIN) return dg_launch_variant<false, false, EPI_PLAIN>(variant, a, lda, b, ldb, M, N, K, epi, st);
+    if (mode == EPI_ACCUM_F32) return dg_launch_variant<false, false, EPI_ACCUM_F32>(variant, a, lda, b, ldb, M, N, K, epi, splits, st);
+    if (mode == EPI_STORE_F32) return dg_launch_variant<false, false, EPI_STORE_F32>(variant, a, lda, b, ldb, M, N, K, epi, splits, st);
+    if (mode == EPI_PLAIN) return dg_launch_variant<false, false, EPI_PLAIN>(variant, a, lda, b, ldb, M, N, K, epi, splits, st);
   }
   return hipErrorInvalidValue;
 }

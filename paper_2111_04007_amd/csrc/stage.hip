@@ -14,7 +14,9 @@
 //               to the caller's fp32 buffer.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
+#include <type_traits>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -124,8 +126,23 @@ struct Workspace {
   size_t ping[2];                // forward layer outputs (discarded)
   size_t dxn, dctx, delta, partial;
   size_t stat_partial;           // partial sums of the gradient statistics (doubles)
+  size_t splitk, splitk_size;    // partial weight gradients of split-K GEMMs (fp32); size 0 if no GEMM splits
   size_t total;
 };
+// Largest split-K partial buffer any of the four weight-gradient GEMMs can ask for, over all
+// reduction lengths cnt*T (cnt = 1..G micro-batches gathered).
+size_t splitk_bytes(const Dims& D) {
+  if (D.dtype != VARUNA_BF16) return 0;
+  const int64_t shapes[4][2] = {{D.h, D.f}, {D.f, D.h}, {D.h, D.h}, {3 * (int64_t)D.h, D.h}};
+  size_t best = 0;
+  for (int cnt = 1; cnt <= D.G; ++cnt)
+    for (const auto& mn : shapes) {
+      const int s = dg_wgrad_splits(mn[0], mn[1], (int64_t)cnt * D.T);
+      if (s > 1) best = std::max(best, (size_t)s * mn[0] * mn[1] * sizeof(float));
+    }
+  return best;
+}
+
 Workspace carve(const Dims& D) {
   Workspace w;
   size_t o = 0;
@@ -156,6 +173,8 @@ Workspace carve(const Dims& D) {
   if (D.f > widest) widest = D.f;
   w.partial = take((size_t)colreduce_chunks(D.T) * widest * sizeof(float));
   w.stat_partial = take((size_t)kStatBlocks * 2 * sizeof(double));
+  w.splitk_size = splitk_bytes(D);
+  w.splitk = take(w.splitk_size);
   w.total = o;
   return w;
 }
@@ -211,8 +230,9 @@ template <typename T> struct GemmDispatch;
 
 template <> struct GemmDispatch<float> {
   static hipError_t run(int op, int mode, int variant, int64_t M, int64_t N, int64_t K, const float* a,
-                        const float* b, const EpiArgs<float>& e, hipStream_t s) {
+                        const float* b, const EpiArgs<float>& e, hipStream_t s, int splits = 1) {
     (void)variant;
+    if (splits != 1) return hipErrorInvalidConfiguration;
     if (op == GEMM_FWD) return launch_gemm_simple<float>(mode, a, K, 1, b, K, 1, M, N, K, e, s);
     if (op == GEMM_DGRAD) return launch_gemm_simple<float>(mode, a, K, 1, b, 1, N, M, N, K, e, s);
     return launch_gemm_simple<float>(mode, a, 1, M, b, 1, N, M, N, K, e, s);
@@ -224,7 +244,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 template <> struct GemmDispatch<bf16> {
   // variant 0: library's choice; -1: force the simple kernel; >0: that MFMA configuration
   static hipError_t run(int op, int mode, int variant, int64_t M, int64_t N, int64_t K, const bf16* a,
-                        const bf16* b, const EpiArgs<bf16>& e, hipStream_t s) {
+                        const bf16* b, const EpiArgs<bf16>& e, hipStream_t s, int splits = 1) {
     const int64_t lda = (op == GEMM_WGRAD) ? M : K;
     const int64_t ldb = (op == GEMM_FWD) ? K : N;
     const bool ptr_ok = aligned16(a) && aligned16(b) && aligned16(e.bias) && aligned16(e.aux_in) &&
@@ -237,8 +257,9 @@ template <> struct GemmDispatch<bf16> {
     }
     if (v >= 5) {
       if (!ptr_ok || !dg_shape_ok(v, M, N, K, lda, ldb)) return hipErrorInvalidConfiguration;
-      return launch_gemm_dma(op, mode, v, a, lda, b, ldb, M, N, K, e, s);
+      return launch_gemm_dma(op, mode, v, a, lda, b, ldb, M, N, K, e, s, splits);
     }
+    if (splits != 1) return hipErrorInvalidConfiguration;
     if (v > 0) {
       if (!ptr_ok || !mg_shape_ok(v, M, N, K, lda, ldb)) return hipErrorInvalidConfiguration;
       return launch_gemm_mfma(op, mode, v, a, lda, b, ldb, M, N, K, e, s);
@@ -423,15 +444,39 @@ struct StageOps {
   // dW += dY^T X for the four matrices of every layer, over the `cnt` micro-batches whose
   // operands sit in ring slots 0..cnt-1: the slots are stacked along the token dimension,
   // so each is ONE GEMM with reduction length cnt*T and one fp32 read-modify-write of dW.
+  // One weight gradient dW[M,N] += A^T B over K tokens.  bf16 shapes with too few output
+  // tiles for the chip cut the reduction into splits whose partial results are added to dW in
+  // a fixed order (deterministic).
+  hipError_t wgrad(int64_t M, int64_t N, int64_t K, const T* a, const T* b, float* dw) {
+    if constexpr (std::is_same<T, bf16>::value) {
+      const int splits = dg_wgrad_splits(M, N, K);
+      if (splits > 1 && (size_t)splits * M * N * sizeof(float) <= S->ws.splitk_size && aligned16(a) && aligned16(b) && aligned16(dw)) {
+        float* part = wsp<float>(S->ws.splitk);
+        hipError_t e;
+        {
+          EpiArgs<T> ea{nullptr, nullptr, nullptr, nullptr, part, N, DropArgs{}, M * N};
+          Bracket br(S, st, VARUNA_K_GEMM_WGRAD, 2.0 * M * N * K, (double)(M * K + N * K) * sizeof(T) + (double)M * N * 4.0 * splits);
+          if ((e = GemmDispatch<T>::run(GEMM_WGRAD, EPI_STORE_F32, 0, M, N, K, a, b, ea, st, splits))) return e;
+        }
+        Bracket br(S, st, VARUNA_K_OTHER, 0, (double)M * N * 4.0 * (splits + 2));
+        return launch_splitk_reduce(part, splits, M * N, dw, st);
+      }
+    }
+    return gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, M, N, K, a, b, nullptr, nullptr, nullptr, nullptr, dw);
+  }
+
+  // dW += dY^T X for the four matrices of every layer, over the `cnt` micro-batches whose
+  // operands sit in ring slots 0..cnt-1: the slots are stacked along the token dimension,
+  // so each is ONE GEMM with reduction length cnt*T and one fp32 read-modify-write of dW.
   hipError_t flush_wgrads(int cnt) {
     hipError_t e;
     const int64_t K = (int64_t)cnt * D.T;
     for (int l = D.L - 1; l >= 0; --l) {
       const LayerArea& A = S->ws.layer[l];
-      if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.h, D.f, K, wsp<T>(A.dyd), wsp<T>(A.g), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_W2)))) return e;
-      if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.f, D.h, K, wsp<T>(A.du), wsp<T>(A.xn2), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_W1)))) return e;
-      if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, D.h, D.h, K, wsp<T>(A.dx1d), wsp<T>(A.ctx), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_WO)))) return e;
-      if ((e = gemm(VARUNA_K_GEMM_WGRAD, GEMM_WGRAD, EPI_ACCUM_F32, 3 * D.h, D.h, K, wsp<T>(A.dqkv), wsp<T>(A.xn1), nullptr, nullptr, nullptr, nullptr, grad(l, VARUNA_P_WQKV)))) return e;
+      if ((e = wgrad(D.h, D.f, K, wsp<T>(A.dyd), wsp<T>(A.g), grad(l, VARUNA_P_W2)))) return e;
+      if ((e = wgrad(D.f, D.h, K, wsp<T>(A.du), wsp<T>(A.xn2), grad(l, VARUNA_P_W1)))) return e;
+      if ((e = wgrad(D.h, D.h, K, wsp<T>(A.dx1d), wsp<T>(A.ctx), grad(l, VARUNA_P_WO)))) return e;
+      if ((e = wgrad(3 * D.h, D.h, K, wsp<T>(A.dqkv), wsp<T>(A.xn1), grad(l, VARUNA_P_WQKV)))) return e;
     }
     return hipSuccess;
   }

@@ -26,7 +26,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="C5", help="C1..C5 (default: the largest stage, C5)")
     ap.add_argument("--micro-batches", type=int, default=0, help="override M (default: the config's)")
-    ap.add_argument("--wgrad-group", type=int, default=4,
+    ap.add_argument("--wgrad-group", type=int, default=8,
                     help="micro-batches per weight-gradient GEMM (library knob; 1 = per micro-batch)")
     ap.add_argument("--stage", choices=("middle", "last"), default="middle",
                     help="middle: M forwards then M recompute+backward calls (the headline step); last: the "

@@ -18,8 +18,12 @@
  *     varuna_stage_destroy and be 256-byte aligned.  The library allocates no
  *     device memory in any call.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
- *     Every compute call only enqueues work on it and returns; nothing
- *     synchronises with the host.  One handle is used from one stream at a time.
+ *     Every compute call only enqueues work and returns; nothing synchronises
+ *     with the host.  All results of a call are ordered on hip_stream: the
+ *     backward calls run their bias-gradient reductions on a stream of the
+ *     library's own (default priority, created at the first backward call),
+ *     forked from and joined back into hip_stream with events inside the call.
+ *     One handle is used from one stream at a time.
  *   - Activations are row-major [T, h], T = micro_batch * seq_len, row index
  *     = batch_index * seq_len + position.  dtype F32: all tensors fp32.
  *     dtype BF16: activations, parameters and dX are bf16; all accumulators,

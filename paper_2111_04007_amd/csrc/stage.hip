@@ -125,6 +125,7 @@ struct Workspace {
   size_t saved_begin, saved_end;
   size_t ping[2];                // forward layer outputs (discarded)
   size_t dxn, dctx, delta, partial;
+  size_t partial_side;           // reduction partials of the bias-gradient sums that run on the side stream
   size_t stat_partial;           // partial sums of the gradient statistics (doubles)
   size_t splitk, splitk_size;    // partial weight gradients of split-K GEMMs (fp32); size 0 if no GEMM splits
   size_t total;
@@ -172,6 +173,7 @@ Workspace carve(const Dims& D) {
   int64_t widest = 3 * (int64_t)D.h;
   if (D.f > widest) widest = D.f;
   w.partial = take((size_t)colreduce_chunks(D.T) * widest * sizeof(float));
+  w.partial_side = take((size_t)colreduce_chunks(D.T) * widest * sizeof(float));
   w.stat_partial = take((size_t)kStatBlocks * 2 * sizeof(double));
   w.splitk_size = splitk_bytes(D);
   w.splitk = take(w.splitk_size);
@@ -196,6 +198,12 @@ struct varuna_stage {
   int kept_mb = -1;  // micro-batch whose internals forward_keep left in the layer areas (-1: none)
   int kept_slot = 0; // ring slot they were written to
   uint64_t seed = 0;  // dropout seed (varuna_stage_set_dropout_seed)
+  // The bias-gradient column sums of the backward pass depend on nothing downstream and are
+  // HBM-bound, so they run on a stream of the library's own beside the GEMM chain (forked and
+  // joined with events inside every backward call; created at the first backward call).
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  bool side_used = false;  // work was forked in the current call and has not been joined yet
   // profiler
   bool prof_on = false;
   std::vector<hipEvent_t> ev;  // pairs
@@ -372,8 +380,32 @@ struct StageOps {
   }
 
   hipError_t colsum(const T* a, float* out, int64_t n) {
-    Bracket br(S, st, VARUNA_K_COLREDUCE, 0, (double)D.T * n * sizeof(T));
-    return launch_colsum<T>(a, out, wsp<float>(S->ws.partial), D.T, n, st);
+    if (S->prof_on || S->side == nullptr) {  // per-kernel timing wants everything on one stream
+      Bracket br(S, st, VARUNA_K_COLREDUCE, 0, (double)D.T * n * sizeof(T));
+      return launch_colsum<T>(a, out, wsp<float>(S->ws.partial), D.T, n, st);
+    }
+    hipError_t e;
+    if ((e = hipEventRecord(S->ev_fork, st))) return e;           // `a` is complete at this point of the caller's stream
+    if ((e = hipStreamWaitEvent(S->side, S->ev_fork, 0))) return e;
+    S->side_used = true;
+    return launch_colsum<T>(a, out, wsp<float>(S->ws.partial_side), D.T, n, S->side);
+  }
+
+  // Creates the side stream on first use (no GPU call happens at stage creation).
+  hipError_t ensure_side() {
+    if (S->side != nullptr) return hipSuccess;
+    hipError_t e;
+    if ((e = hipStreamCreateWithFlags(&S->side, hipStreamNonBlocking))) return e;
+    if ((e = hipEventCreateWithFlags(&S->ev_fork, hipEventDisableTiming))) return e;
+    return hipEventCreateWithFlags(&S->ev_join, hipEventDisableTiming);
+  }
+  // The caller's stream waits for everything forked since the last join.
+  hipError_t join_side() {
+    if (!S->side_used) return hipSuccess;
+    S->side_used = false;
+    hipError_t e;
+    if ((e = hipEventRecord(S->ev_join, S->side))) return e;
+    return hipStreamWaitEvent(st, S->ev_join, 0);
   }
 
   // One layer backward for ring slot rs.  x: the layer's input; the gradient of its output
@@ -521,6 +553,7 @@ struct StageOps {
   hipError_t backward(int mb, const T* dy_in, T* dx_out, bool recompute_first) {
     hipError_t e;
     const int rs = S->pending;
+    if ((e = ensure_side())) return e;
     if (recompute_first && (e = recompute(mb, nullptr, rs))) return e;
     {  // the upstream gradient joins the top layer's dy ring
       Bracket br(S, st, VARUNA_K_OTHER, 0, 2.0 * D.E * sizeof(T));
@@ -531,6 +564,7 @@ struct StageOps {
       T* dx = (l == 0) ? dx_out : wsp<T>(S->ws.layer[l - 1].dy) + (size_t)rs * D.E;
       if ((e = layer_backward(l, mb, x, dx, S->ws.layer[l], rs))) return e;
     }
+    if ((e = join_side())) return e;   // the bias gradients are complete when this call's work is
     if (++S->pending == D.G) {
       if ((e = flush_wgrads(S->pending))) return e;
       S->pending = 0;
@@ -643,6 +677,12 @@ varuna_status_t varuna_stage_create(const varuna_stage_config_t* cfg, const void
 varuna_status_t varuna_stage_destroy(varuna_stage_t* st) {
   if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
   for (hipEvent_t e : st->ev) (void)hipEventDestroy(e);
+  if (st->side) {
+    (void)hipStreamSynchronize(st->side);
+    (void)hipStreamDestroy(st->side);
+    (void)hipEventDestroy(st->ev_fork);
+    (void)hipEventDestroy(st->ev_join);
+  }
   delete st;
   return VARUNA_OK;
 }

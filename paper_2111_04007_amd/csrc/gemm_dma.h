@@ -160,6 +160,9 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
+  // the epilogues swizzle 16-byte chunks of a staged fp32 row by the low four bits of the row
+  // number, which needs rows of whole groups of 16 chunks
+  static_assert(WM % 32 == 0 && WN % 64 == 0, "wave sub-tile: rows in 32s, columns in 64s");
   constexpr int STAGE_ELEMS = (BM + BN) * DG_BK;
   extern __shared__ __attribute__((aligned(16))) unsigned char dg_smem[];
   bf16* smem = reinterpret_cast<bf16*>(dg_smem);  // [2][A tile | B tile]

@@ -167,34 +167,51 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
 #pragma unroll
       for (int db = 0; db < C::DB; ++db) vtr[t][db] = at_tr_frag<D>(sv, 16 * t, db * 32, lane);
     __builtin_amdgcn_sched_barrier(0);
+    // Raw scores stay in the accumulators until the exponential: the row maximum is taken on
+    // them (the scale is positive), and scale and shift fold into one fused multiply-add.
+    // Only key blocks that straddle the diagonal pay for the mask.
     float p[2][16];
     float mx = -INFINITY;
-    const bool need_mask = CAUSAL && (k0 + 63 > qw);
+    if (CAUSAL && k0 + 63 > qw) {
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + sb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+          if (key > query) sc[sb][r] = -INFINITY;
+        }
+    }
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = sc[sb][r] * scale_log2e;
-        if (need_mask) {
-          const int key = k0 + sb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-          if (key > query) v = -INFINITY;
-        }
-        p[sb][r] = v;
-        mx = fmaxf(mx, v);
-      }
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[sb][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m, mx);           // finite: key 0 is visible to every query
-    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-    m = m_new;
+    // The running reference m only moves when a row's maximum grows by more than 2^8: until
+    // then the exponentials are taken against the old reference (they stay below 256, l and
+    // the output carry the same factor and the final division removes it), and the block
+    // skips rescaling the output accumulators.  Key 0 is visible to every query, so the
+    // first block always sets a finite reference.
+    const float m_cand = fmaxf(m, mx * scale_log2e);
+    const bool grow = m_cand > m + 8.0f;
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+      const float m_new = grow ? m_cand : m;
+      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+      m = m_new;
+      l *= alpha;
+#pragma unroll
+      for (int i = 0; i < C::DB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+    }
     float psum = 0.f;
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        p[sb][r] = __builtin_amdgcn_exp2f(p[sb][r] - m_new);
+        p[sb][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[sb][r], scale_log2e, -m));
         psum += p[sb][r];
       }
-    l = l * alpha + psum;   // the softmax is normalised before the dropout
+    l += psum;   // the softmax is normalised before the dropout
     if (DROP) {
       // this lane's 16 probabilities of a 32-key block are 4 groups of 4 consecutive keys of
       // ONE mask row (its query): one generator call per group
@@ -209,10 +226,6 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
             if (!drop_keep(drop, w, e)) p[sb][4 * g + e] = 0.f;
         }
     }
-#pragma unroll
-    for (int i = 0; i < C::DB; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) {
@@ -346,11 +359,22 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
           for (int e = 0; e < 4; ++e) dp[4 * g + e] = drop_keep(drop, w, e) ? dp[4 * g + e] * drop.scale : 0.f;
         }
       }
+      // Below d = 128 only key blocks that straddle or follow the diagonal pay for the mask
+      // (a branch on the wave's position); at d = 128 the kernel sits at the register limit,
+      // the branch costs a spill, and masking every block was measured faster.
+      constexpr bool MASK_BRANCH = D < 128;
+      if (MASK_BRANCH && need_mask) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + sb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+          if (key > query) sc[r] = -INFINITY;
+        }
+      }
       float ds[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float pr = __builtin_amdgcn_exp2f(sc[r] * scale_log2e - l2);
-        if (need_mask) {
+        float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r], scale_log2e, -l2));
+        if (!MASK_BRANCH && need_mask) {
           const int key = k0 + sb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
           if (key > query) pr = 0.f;
         }

@@ -124,10 +124,14 @@ def test_colsum(dtype, rows, n):
     assert O.rel_l2(to_f64(out), 1.0 + to_f64(a).sum(axis=0)) <= 1e-5
 
 
-def run_attention_case(dtype, b, s, heads, d, causal, variant, seed=20):
+def run_attention_case(dtype, b, s, heads, d, causal, variant, seed=20, key_ramp=None):
     h = heads * d
     sh = O.StageShape(1, h, heads, s, b, 4 * h, bool(causal))
     qkv = rnd((b * s, 3 * h), dtype, seed, 1.0)
+    if key_ramp is not None:   # keys grow along the sequence: row maxima keep rising from key block to key block
+        pos = torch.arange(b * s, device="cuda") % s
+        ramp = key_ramp[0] + (key_ramp[1] - key_ramp[0]) * pos.to(torch.float32) / max(1, s - 1)
+        qkv[:, h:2 * h] = (qkv[:, h:2 * h].float() * ramp[:, None]).to(qkv.dtype)
     dctx = rnd((b * s, h), dtype, seed + 1)
     ctx = torch.empty((b * s, h), dtype=DT[dtype], device="cuda")
     lse = torch.empty(b * heads * s, dtype=torch.float32, device="cuda")
@@ -178,6 +182,14 @@ def test_attention_bf16_simple(b, s, heads, d, causal):
 def test_attention_bf16_mfma(b, s, heads, d, causal):
     """MFMA kernels: every head dim, causal and bidirectional, 1 to 4 query/key blocks."""
     run_attention_case("bf16", b, s, heads, d, causal, variant=1, seed=30 + d)
+
+
+@pytest.mark.parametrize("b,s,heads,d,causal", [(1, 512, 2, 64, 0), (1, 512, 1, 128, 1), (1, 384, 1, 96, 0)])
+def test_attention_bf16_mfma_rising_row_maxima(b, s, heads, d, causal):
+    """Keys whose norm grows 8x along the sequence: the scores of later key blocks exceed the
+    earlier maxima by more than 2^8 for many rows and by less for others, so both branches of
+    the forward kernel's thresholded online-softmax rescale run after the first block."""
+    run_attention_case("bf16", b, s, heads, d, causal, variant=1, seed=70 + d, key_ramp=(0.5, 4.0))
 
 
 def test_attention_mfma_rejects_unsupported_shape():

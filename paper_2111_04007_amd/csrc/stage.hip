@@ -473,9 +473,6 @@ struct StageOps {
     return hipSuccess;
   }
 
-  // dW += dY^T X for the four matrices of every layer, over the `cnt` micro-batches whose
-  // operands sit in ring slots 0..cnt-1: the slots are stacked along the token dimension,
-  // so each is ONE GEMM with reduction length cnt*T and one fp32 read-modify-write of dW.
   // One weight gradient dW[M,N] += A^T B over K tokens.  bf16 shapes with too few output
   // tiles for the chip cut the reduction into splits whose partial results are added to dW in
   // a fixed order (deterministic).

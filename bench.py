@@ -22,8 +22,8 @@ sys.path.insert(0, ROOT)
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C5", help="C1..C5 (default: the largest stage, C5)")
     ap.add_argument("--micro-batches", type=int, default=0, help="override M (default: the config's)")
     ap.add_argument("--wgrad-group", type=int, default=8,
@@ -154,14 +154,20 @@ def main():
 
     for _ in range(args.warmup):
         step()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
+        marks[i].record(stream)     # per-step spread (median, min); the headline is the wall time of all steps
         step()
+    marks[args.steps].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_step = wall * 1e3 / args.steps
     ms_mb = ms_step / M
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    ms_step_median = per_step[len(per_step) // 2] if len(per_step) % 2 else 0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2])
+    ms_step_min = per_step[0]
 
     # separate forward / (recompute+)backward timing with events on the same stream
     st.grad_accum_reset(stream)
@@ -268,7 +274,8 @@ def main():
                         (f" with dropout {cfg.dropout_p}" if cfg.dropout_p > 0 else ""), "n_layers": cfg.n_layers, "hidden": cfg.hidden, "n_heads": cfg.n_heads,
             "seq_len": cfg.seq_len, "micro_batch": cfg.micro_batch, "n_micro_batches": M,
             "mlp_hidden": cfg.mlp_hidden, "causal": cfg.causal, "wgrad_group": cfg.wgrad_group, "dropout_p": cfg.dropout_p,
-            "ms_per_micro_batch": ms_mb, "ms_forward_per_micro_batch": ms_f,
+            "ms_per_micro_batch": ms_mb, "ms_per_step_median": ms_step_median, "ms_per_step_min": ms_step_min,
+            "ms_forward_per_micro_batch": ms_f,
             ("ms_backward_per_micro_batch" if last else "ms_recompute_backward_per_micro_batch"): ms_rb,
             "frac_of_bf16_mfma_peak": frac_peak, "peak_tflops_used": flops.MI355X_BF16_DENSE_PEAK / 1e12,
             "useful_tflops_paper_convention": useful_flops_mb * M / (ms_step * 1e-3) / 1e12,

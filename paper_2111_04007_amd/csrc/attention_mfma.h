@@ -110,8 +110,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
   __shared__ __attribute__((aligned(16))) bf16 sk[C::TILE];
   __shared__ __attribute__((aligned(16))) bf16 sv[C::TILE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
-  const int qb = gridDim.x - 1 - blockIdx.x;  // long (late) query blocks first under the causal mask
-  const int head = blockIdx.y, bi = blockIdx.z;
+  // Grid: x = (batch, head), y = query block.  Workgroups are dispatched in x-fastest order,
+  // so under the causal mask every head's longest (latest) query blocks start first and only
+  // short ones are left at the end of the launch; and because consecutive workgroups go round
+  // the 8 XCDs, all query blocks of one head (same x mod 8) share one XCD's L2 for K and V.
+  const int qb = gridDim.y - 1 - blockIdx.y;
+  const int head = blockIdx.x % heads, bi = blockIdx.x / heads;
   const int h = heads * D;
   const int64_t ld = 3 * (int64_t)h;
   const bf16* base = qkv + (int64_t)bi * s * ld + head * D;
@@ -274,8 +278,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
   __shared__ __attribute__((aligned(16))) bf16 sk[C::TILE];
   __shared__ __attribute__((aligned(16))) bf16 sv[C::TILE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
-  const int qb = gridDim.x - 1 - blockIdx.x;
-  const int head = blockIdx.y, bi = blockIdx.z;
+  const int qb = gridDim.y - 1 - blockIdx.y;   // grid as in the forward kernel: long query blocks of every head first
+  const int head = blockIdx.x % heads, bi = blockIdx.x / heads;
   const int h = heads * D;
   const int64_t ld = 3 * (int64_t)h;
   const bf16* base = qkv + (int64_t)bi * s * ld + head * D;
@@ -419,8 +423,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
   __shared__ __attribute__((aligned(16))) bf16 sq[C::TILE];
   __shared__ __attribute__((aligned(16))) bf16 sg[C::TILE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
-  const int kblk = blockIdx.x;  // early key blocks (most queries under the causal mask) first
-  const int head = blockIdx.y, bi = blockIdx.z;
+  // grid: x = (batch, head), y = key block; early key blocks (most queries under the causal
+  // mask) of every head are dispatched first
+  const int kblk = blockIdx.y;
+  const int head = blockIdx.x % heads, bi = blockIdx.x / heads;
   const int h = heads * D;
   const int64_t ld = 3 * (int64_t)h;
   const bf16* base = qkv + (int64_t)bi * s * ld + head * D;
@@ -572,7 +578,7 @@ inline bool attn_mfma_supported(int s, int d) { return (d == 64 || d == 96 || d 
 template <int D, bool DROP>
 inline hipError_t attn_fwd_mfma_d(const bf16* qkv, bf16* ctx, float* lse, int b, int s, int heads, int causal,
                                   const DropArgs& drop, hipStream_t st) {
-  dim3 grid((unsigned)(s / 128), (unsigned)heads, (unsigned)b);
+  dim3 grid((unsigned)(heads * b), (unsigned)(s / 128));
   const float sl = 1.4426950408889634f / sqrtf((float)D);
   if (causal) hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, true, DROP>), grid, dim3(256), 0, st, qkv, ctx, lse, s, heads, sl, drop);
   else hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, false, DROP>), grid, dim3(256), 0, st, qkv, ctx, lse, s, heads, sl, drop);
@@ -591,7 +597,7 @@ inline hipError_t launch_attention_fwd_mfma(const bf16* qkv, bf16* ctx, float* l
 template <int D, bool DROP>
 inline hipError_t attn_bwd_mfma_d(const bf16* qkv, const bf16* ctx, const float* lse, const bf16* dctx, bf16* dqkv,
                                   float* delta, int b, int s, int heads, int causal, const DropArgs& drop, hipStream_t st) {
-  dim3 grid((unsigned)(s / 128), (unsigned)heads, (unsigned)b);
+  dim3 grid((unsigned)(heads * b), (unsigned)(s / 128));
   const float sc = 1.0f / sqrtf((float)D), sl = 1.4426950408889634f * sc;
   if (causal) {
     hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, true, DROP>), grid, dim3(256), 0, st, qkv, ctx, lse, dctx, dqkv, delta, s, heads, sc, sl, drop);

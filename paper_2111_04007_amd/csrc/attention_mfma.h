@@ -92,6 +92,36 @@ __device__ __forceinline__ void at_mfma_acc(floatx16& acc, const bf16x8& a, cons
 }
 __device__ __forceinline__ void at_mfma_settle() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
 
+// Value of lane (4*(lane/4) + j) of the same lane quad, j known at compile time after
+// unrolling (a DPP quad permutation: no LDS, no wait).
+__device__ __forceinline__ uint32_t at_quad_bcast(uint32_t v, int j) {
+  switch (j & 3) {
+    case 0: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x00, 0xf, 0xf, false);
+    case 1: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x55, 0xf, 0xf, false);
+    case 2: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xaa, 0xf, 0xf, false);
+    default: return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xff, 0xf, 0xf, false);
+  }
+}
+
+// Dropout mask words for a lane that owns ONE mask row (its query) and, per 32-key block, the
+// four 4-key groups g = 0..3 of that row.  The four lanes of a quad own the four rows of the
+// same 4x4 mask patches, so each lane generates only the patch of group g = lane%4 and the
+// quad exchanges words: out[g] = word (lane%4) of the patch generated by quad lane g.
+// row_patch must be the same in all four lanes; col_patch0 is group 0's patch column, group g
+// lies two patch columns further per step.
+__device__ __forceinline__ void at_drop_row_words(const DropArgs& drop, uint32_t row_patch, uint32_t col_patch0, int lane,
+                                                  uint32_t out[4]) {
+  const int ql = lane & 3;
+  uint32_t own[4];
+  drop_patch(drop, row_patch, col_patch0 + 2u * (uint32_t)ql, own);
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const uint32_t t0 = at_quad_bcast(own[0], g), t1 = at_quad_bcast(own[1], g);
+    const uint32_t t2 = at_quad_bcast(own[2], g), t3 = at_quad_bcast(own[3], g);
+    out[g] = ql == 0 ? t0 : (ql == 1 ? t1 : (ql == 2 ? t2 : t3));
+  }
+}
+
 __device__ __forceinline__ bf16x8 at_pack8(const float* p) {
   bf16x8 r;
 #pragma unroll
@@ -218,17 +248,18 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16* __res
     l += psum;   // the softmax is normalised before the dropout
     if (DROP) {
       // this lane's 16 probabilities of a 32-key block are 4 groups of 4 consecutive keys of
-      // ONE mask row (its query): one generator call per group
+      // ONE mask row (its query): one generator call per block, shared within the lane quad
       const uint32_t drow = (uint32_t)(((int64_t)bi * heads + head) * s + query);
 #pragma unroll
-      for (int sb = 0; sb < 2; ++sb)
+      for (int sb = 0; sb < 2; ++sb) {
+        uint32_t w[4];
+        at_drop_row_words(drop, drow >> 2, (uint32_t)(k0 + sb * 32 + 4 * hf) >> 2, lane, w);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const uint32_t w = drop_row_word(drop, drow, (uint32_t)(k0 + sb * 32 + 8 * g + 4 * hf) >> 2);
+        for (int g = 0; g < 4; ++g)
 #pragma unroll
           for (int e = 0; e < 4; ++e)
-            if (!drop_keep(drop, w, e)) p[sb][4 * g + e] = 0.f;
-        }
+            if (!drop_keep(drop, w[g], e)) p[sb][4 * g + e] = 0.f;
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -356,12 +387,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16* __
       for (int db = 0; db < C::DB; ++db) ktr[0][db] = at_tr_frag<D>(sk, sb * 32, db * 32, lane);
       __builtin_amdgcn_sched_barrier(0);
       if (DROP) {  // dP = dropout'(dO V^T): same mask words as the forward kernel
+        uint32_t w[4];
+        at_drop_row_words(drop, (uint32_t)sidx >> 2, (uint32_t)(k0 + sb * 32 + 4 * hf) >> 2, lane, w);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const uint32_t w = drop_row_word(drop, (uint32_t)sidx, (uint32_t)(k0 + sb * 32 + 8 * g + 4 * hf) >> 2);
+        for (int g = 0; g < 4; ++g)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) dp[4 * g + e] = drop_keep(drop, w, e) ? dp[4 * g + e] * drop.scale : 0.f;
-        }
+          for (int e = 0; e < 4; ++e) dp[4 * g + e] = drop_keep(drop, w[g], e) ? dp[4 * g + e] * drop.scale : 0.f;
       }
       // Below d = 128 only key blocks that straddle or follow the diagonal pay for the mask
       // (a branch on the wave's position); at d = 128 the kernel sits at the register limit,
@@ -515,14 +546,21 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
       }
       __builtin_amdgcn_sched_barrier(0);
       float pr[16], ds[16];
+      // Each group g of 4 consecutive queries is the 4 rows of one mask patch and this lane's
+      // key one of its columns; the four lanes of a quad share the patch column, so each
+      // generates the patch of group g = lane%4 only and the quad exchanges the words.
+      uint32_t own[4];
+      if (DROP) drop_patch(drop, ((uint32_t)(sbase + q0 + sb * 32 + 4 * hf) >> 2) + 2u * (uint32_t)(lane & 3), (uint32_t)key >> 2, own);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int ql = sb * 32 + 8 * g + 4 * hf;  // 4 consecutive queries of the tile
         const floatx4 l4 = *reinterpret_cast<const floatx4*>(&sstat[0][ql]);
         const floatx4 d4 = *reinterpret_cast<const floatx4*>(&sstat[1][ql]);
         uint32_t mw[4];
-        // the 4 consecutive queries are the 4 rows of one mask patch, this lane's key one of its columns
-        if (DROP) drop_patch(drop, (uint32_t)(sbase + q0 + ql) >> 2, (uint32_t)key >> 2, mw);
+        if (DROP) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) mw[e] = at_quad_bcast(own[e], g);
+        }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * g + e;

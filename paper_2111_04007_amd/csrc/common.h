@@ -45,6 +45,19 @@ __device__ __forceinline__ float gelu_tanh_grad_f(float u) {
   float dinner = c * (1.0f + 3.0f * a * u * u);
   return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * dinner;
 }
+// The same two functions for the bf16 GEMM epilogues, written on the logistic form
+// 0.5 (1 + tanh z) = 1 / (1 + e^{-2z}) with the hardware exp2 and reciprocal (relative error
+// about 1e-6, far below the bf16 rounding of the result; no cancellation for large |u|: the
+// exponential overflows to +inf or underflows to 0 and the reciprocal gives 0 or 1).
+__device__ __forceinline__ float gelu_logistic_f(float u) {
+  const float k1 = -2.3022081983f, k3 = -0.10294324f;   // -2 c log2(e) and that times a
+  return u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(u * (k1 + k3 * u * u)));
+}
+__device__ __forceinline__ float gelu_logistic_grad_f(float u) {
+  const float k1 = -2.3022081983f, k3 = -0.10294324f, c = 0.7978845608028654f, a = 0.044715f;
+  const float s = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(u * (k1 + k3 * u * u)));
+  return s + u * s * (1.0f - s) * (2.0f * c * (1.0f + 3.0f * a * u * u));
+}
 
 // ---- dropout masks --------------------------------------------------------------------
 // Masks are a pure function of (seed, micro-batch, layer, site, element), so the recompute

@@ -58,7 +58,7 @@ __device__ __forceinline__ void mg_epilogue4(const EpiArgs<bf16>& e, int64_t m, 
       *reinterpret_cast<bf16x4*>(e.aux_out + idx) = uv;
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] = gelu_tanh_f(o[i]);
+    for (int i = 0; i < 4; ++i) o[i] = gelu_logistic_f(o[i]);
   }
   if (MODE == EPI_BIAS_RES) {
     if (e.drop.thr != 0) {  // n is a multiple of 4: one patch row covers the four columns
@@ -73,7 +73,7 @@ __device__ __forceinline__ void mg_epilogue4(const EpiArgs<bf16>& e, int64_t m, 
   if (MODE == EPI_DGELU) {
     bf16x4 uv = *reinterpret_cast<const bf16x4*>(e.aux_in + idx);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] *= gelu_tanh_grad_f((float)uv[i]);
+    for (int i = 0; i < 4; ++i) o[i] *= gelu_logistic_grad_f((float)uv[i]);
   }
   bf16x4 ov;
 #pragma unroll
@@ -101,7 +101,7 @@ __device__ __forceinline__ void mg_epilogue8(const EpiArgs<bf16>& e, int64_t m, 
       *reinterpret_cast<bf16x8*>(e.aux_out + idx) = uv;
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) o[i] = gelu_tanh_f(o[i]);
+    for (int i = 0; i < 8; ++i) o[i] = gelu_logistic_f(o[i]);
   }
   if (MODE == EPI_BIAS_RES) {
     if (e.drop.thr != 0) {  // n is a multiple of 8: two patches of this row
@@ -120,7 +120,7 @@ __device__ __forceinline__ void mg_epilogue8(const EpiArgs<bf16>& e, int64_t m, 
   if (MODE == EPI_DGELU) {
     const bf16x8 uv = *reinterpret_cast<const bf16x8*>(e.aux_in + idx);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) o[i] *= gelu_tanh_grad_f((float)uv[i]);
+    for (int i = 0; i < 8; ++i) o[i] *= gelu_logistic_grad_f((float)uv[i]);
   }
   bf16x8 ov;
 #pragma unroll

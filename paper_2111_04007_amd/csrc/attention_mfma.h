@@ -508,41 +508,49 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
     // workgroup's first tile only, the mask zeroes its contribution, and a branch around the
     // products makes the compiler copy all accumulators.)
     const bool need_mask = CAUSAL && (q0 < kw + 31);
+    // Order of one 64-query tile (one wave per SIMD: nothing but this order overlaps the LDS
+    // with the matrix pipe).  Per 32-query half `sb`: the row fragments of Q and dO for S and
+    // dP (all k-steps) and the first half of the transposed fragments for dV/dK go out as one
+    // batch; S and dP are multiplied while the tail of that batch is still landing; the second
+    // half of the transposed fragments is fetched under the softmax arithmetic; and the row
+    // fragments of the NEXT half are fetched before this half's dV/dK products are issued, so
+    // they land under those products.  The scheduling fences keep it that way (left alone,
+    // the compiler pairs every read with its product and waits for each one).
+    bf16x8 qfr[C::KD], gfr[C::KD];
+    auto fetch_rows = [&](int sb) {
+#pragma unroll
+      for (int t = 0; t < C::KD; ++t) {
+        qfr[t] = at_row_frag<D>(sq, sb * 32, 16 * t, lane);
+        gfr[t] = at_row_frag<D>(sg, sb * 32, 16 * t, lane);
+      }
+    };
+    // (At d = 64 the kernel fits two waves per SIMD, which overlap by themselves; fetching a
+    // half ahead would cost the registers that allow it.)
+    constexpr bool AHEAD = D > 64;
+    if (AHEAD) fetch_rows(0);
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) {
-      // The LDS fragments of each group of products are fetched as one batch ahead of the
-      // products (the scheduling fences keep it that way: left alone, the compiler pairs
-      // every read with its product and waits for each one, which exposes the LDS latency
-      // once per product with one wave per SIMD).
-      floatx16 sc, dp;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
-      constexpr int KH = (C::KD + 1) / 2;  // k-steps per batch (two batches bound the registers held by fragments)
-#pragma unroll
-      for (int t0 = 0; t0 < C::KD; t0 += KH) {
-        bf16x8 qfr[KH], gfr[KH];
-#pragma unroll
-        for (int t = 0; t < KH; ++t)
-          if (t0 + t < C::KD) {
-            qfr[t] = at_row_frag<D>(sq, sb * 32, 16 * (t0 + t), lane);
-            gfr[t] = at_row_frag<D>(sg, sb * 32, 16 * (t0 + t), lane);
-          }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int t = 0; t < KH; ++t)
-          if (t0 + t < C::KD) {
-            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr[t], kf[t0 + t], sc, 0, 0, 0);
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gfr[t], vf[t0 + t], dp, 0, 0, 0);
-          }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      // transposed dO / Q fragments of the second pair of products, first half: in flight
-      // during the softmax arithmetic
+      if (!AHEAD) fetch_rows(sb);
       bf16x8 gtr[2][C::DB], qtr[2][C::DB];
 #pragma unroll
       for (int db = 0; db < C::DB; ++db) {
         gtr[0][db] = at_tr_frag<D>(sg, sb * 32, db * 32, lane);
         qtr[0][db] = at_tr_frag<D>(sq, sb * 32, db * 32, lane);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      floatx16 sc, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int t = 0; t < C::KD; ++t) {
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr[t], kf[t], sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gfr[t], vf[t], dp, 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int db = 0; db < C::DB; ++db) {
+        gtr[1][db] = at_tr_frag<D>(sg, sb * 32 + 16, db * 32, lane);
+        qtr[1][db] = at_tr_frag<D>(sq, sb * 32 + 16, db * 32, lane);
       }
       __builtin_amdgcn_sched_barrier(0);
       float pr[16], ds[16];
@@ -573,13 +581,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
         }
       }
       __builtin_amdgcn_sched_barrier(0);
-      // second half of the fragments: in flight during the first half's products
-#pragma unroll
-      for (int db = 0; db < C::DB; ++db) {
-        gtr[1][db] = at_tr_frag<D>(sg, sb * 32 + 16, db * 32, lane);
-        qtr[1][db] = at_tr_frag<D>(sq, sb * 32 + 16, db * 32, lane);
+      if (AHEAD && sb == 0) {  // the second half's row fragments: in flight during this half's dV/dK products
+        fetch_rows(1);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const bf16x8 pf = at_pack8(&pr[8 * t]);
@@ -594,6 +599,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
     }
   }
   at_mfma_settle();
+  __builtin_amdgcn_sched_barrier(0);  // the reads of dK/dV below stay below the wait
   bf16* krow = dqkv + ((int64_t)bi * s + key) * ld + h + head * D;
   bf16* vrow = krow + h;
 #pragma unroll

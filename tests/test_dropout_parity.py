@@ -43,6 +43,17 @@ def test_dropout_bf16_small(d, causal):
     st.close()
 
 
+@pytest.mark.parametrize("d,causal", [(64, False), (64, True), (96, False), (96, True), (128, False), (128, True)])
+def test_dropout_bf16_long_sequence_every_kernel_variant(d, causal):
+    """Every (head dim, causal) instantiation of the dropout attention kernels at a sequence
+    of 8 query / 16 key blocks (the small cases above have 2 / 4), one layer, one micro-batch."""
+    heads = 4
+    cfg = synth.StageConfig(f"long-bf16-d{d}-{'causal' if causal else 'bidir'}-dropout", 1, heads * d, heads, 1024, 1, 1,
+                            4 * heads * d, causal, "bf16", 0.02, seed=40 + d + int(causal), dropout_p=0.15)
+    st, _, _ = _run(cfg)
+    st.close()
+
+
 def test_dropout_bf16_grouped_weight_gradients_and_interleaved_order():
     cfg = synth.StageConfig("small-bf16-dropout-g2", 2, 256, 4, 256, 2, 3, 1024, True, "bf16", 0.02, seed=31,
                             wgrad_group=2, dropout_p=0.2)

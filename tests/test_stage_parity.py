@@ -204,6 +204,37 @@ def test_accumulation_reset_and_determinism():
         s.close()
 
 
+@pytest.mark.parametrize("name", ["C2", "C4"])
+def test_bf16_run_to_run_determinism_at_full_shape(name):
+    """The bf16 path (MFMA GEMMs with split-K weight gradients, MFMA attention, bias-gradient
+    sums on the side stream, grouped weight-gradient GEMMs) gives bit-identical outputs, input
+    gradients and accumulated gradients on two independent runs: nothing in it adds floats
+    in an order that depends on timing."""
+    cfg = CONFIGS[name].replace(n_micro_batches=2, wgrad_group=2)
+    params, xs, dys = synth.device_random_stage(cfg, "cuda:0", 2)
+
+    def run():
+        st = B.Stage(cfg, "cuda:0", params_flat=params)
+        ys = [torch.empty_like(xs[0]) for _ in range(2)]
+        dxs = [torch.empty_like(xs[0]) for _ in range(2)]
+        st.grad_accum_reset()
+        for m in range(2):
+            st.forward(m, xs[m], ys[m])
+        for m in range(2):
+            st.backward_recompute(m, dys[m], dxs[m])
+        st.grad_flush()
+        torch.cuda.synchronize()
+        g = st.grads.clone()
+        st.close()
+        return ys, dxs, g
+
+    ya, dxa, ga = run()
+    yb, dxb, gb = run()
+    assert torch.isfinite(ga).all()
+    assert torch.equal(ga, gb)
+    assert all(torch.equal(a, b) for a, b in zip(ya + dxa, yb + dxb))
+
+
 def test_state_error_after_consumed_slot():
     cfg = CONFIGS["C1"]
     st = B.Stage(cfg)

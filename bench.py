@@ -43,14 +43,20 @@ def parse():
     ap.add_argument("--tail", action="store_true",
                     help="instead of the step benchmark, time the mini-batch tail (gradient statistics + Adam "
                          "step over the stage's parameters) and print its HBM roofline")
+    ap.add_argument("--ceiling", action="store_true",
+                    help="instead of the step benchmark, measure what the matrix cores sustain when fed from registers "
+                         "only (v_mfma_f32_32x32x16_bf16 on normally distributed and on all-zero operands)")
+    ap.add_argument("--no-ungrouped", action="store_true",
+                    help="skip the second measurement of the same step with wgrad_group=1 (the configuration as "
+                         "specified: weight gradients accumulated after every micro-batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
     return ap.parse_args()
 
 
 def cpu_baseline(cfg):
-    """The fp64 oracle as it stands, on a bounded sample of the same workload:
-    one layer, one micro-batch, sequence shortened so it costs ~10-30 s."""
+    """The fp64 oracle as it stands on ONE micro-batch of the benchmarked stage (all layers,
+    full sequence): forward + backward = 3 of the 4 forward units a GPU micro-batch costs."""
     import numpy as np
     from oracle import stage_oracle as O
     try:
@@ -58,35 +64,141 @@ def cpu_baseline(cfg):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    h, f = cfg.hidden, cfg.mlp_hidden
-    budget = 8.0e12  # FLOPs of fp64 work to aim for (about 10-20 s on 16 cores)
-    per_token = 3.0 * 2.0 * h * (4 * h + 2 * f)
-    s = cfg.seq_len
-    while s > 64 and per_token * s * cfg.micro_batch > budget:
-        s //= 2
-    b = cfg.micro_batch
-    while b > 1 and per_token * s * b > budget:
-        b //= 2
-    sh = O.StageShape(1, h, cfg.n_heads, s, b, f, cfg.causal, cfg.ln_eps)
+    h, f, s, b = cfg.hidden, cfg.mlp_hidden, cfg.seq_len, cfg.micro_batch
+    sh = O.StageShape(cfg.n_layers, h, cfg.n_heads, s, b, f, cfg.causal, cfg.ln_eps)
     rng = np.random.default_rng(cfg.seed)
-    p = {k: rng.standard_normal(shp) * cfg.w_std for k, shp in O.param_shapes(sh).items()}
-    p["ln1_g"] += 1.0
-    p["ln2_g"] += 1.0
+    params = []
+    for _ in range(cfg.n_layers):
+        p = {k: rng.standard_normal(shp) * cfg.w_std for k, shp in O.param_shapes(sh).items()}
+        p["ln1_g"] += 1.0
+        p["ln2_g"] += 1.0
+        params.append(p)
     x = rng.standard_normal((sh.tokens, h))
     dy = rng.standard_normal((sh.tokens, h))
     t0 = time.perf_counter()
-    y, caches = O.stage_forward(x, [p], sh)
-    O.stage_backward(dy, [p], caches, sh)
+    y, caches = O.stage_forward(x, params, sh)
+    O.stage_backward(dy, params, caches, sh)
     dt = time.perf_counter() - t0
     attn = 4.0 * sh.tokens * s * h * (0.5 if cfg.causal else 1.0)
-    useful = 3.0 * (2.0 * sh.tokens * h * (4 * h + 2 * f) + attn)
+    useful = 3.0 * cfg.n_layers * (2.0 * sh.tokens * h * (4 * h + 2 * f) + attn)
     return {
         "value": useful / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-        "sample": f"fp64 numpy oracle, 1 layer of {cfg.name}, micro-batch {b} x seq {s} "
-                  f"(of {cfg.micro_batch} x {cfg.seq_len}), forward+backward = 3 forward units, "
-                  f"{dt:.1f} s wall",
-        "seconds": dt, "host_cpus": os.cpu_count(),
+        "sample": f"fp64 numpy oracle, one whole micro-batch of {cfg.name} ({cfg.n_layers} layers, micro-batch {b} x seq {s}), "
+                  f"forward+backward = 3 forward units, {dt:.1f} s wall = {dt * 1e3:.0f} ms per micro-batch",
+        "seconds": dt, "ms_per_micro_batch": dt * 1e3, "host_cpus": os.cpu_count(),
     }
+
+
+class GpuSensors:
+    """Samples the GPU's own power and clock sensors (hwmon files of the amdgpu driver, read-only)
+    from a host thread while a timed region runs: the evidence for what clock the chip holds
+    under a given load.  Reports nulls if the box exposes no such files."""
+
+    def __init__(self, period_s=0.05):
+        import glob
+        self.period = period_s
+        self.files = {}
+        for d in sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*")):
+            for key, names in (("power_uw", ("power1_average", "power1_input")), ("sclk_hz", ("freq1_input",)),
+                               ("cap_uw", ("power1_cap",))):
+                for n in names:
+                    f = os.path.join(d, n)
+                    if key not in self.files and os.path.exists(f):
+                        self.files[key] = f
+            if self.files:
+                break
+        self.samples = {"power_uw": [], "sclk_hz": []}
+        self._stop = None
+        self._thread = None
+
+    @staticmethod
+    def _read(path):
+        try:
+            with open(path) as fh:
+                return float(fh.read().strip())
+        except (OSError, ValueError):
+            return None
+
+    def __enter__(self):
+        import threading
+        self.samples = {"power_uw": [], "sclk_hz": []}
+        self._stop = threading.Event()
+
+        def loop():
+            while not self._stop.is_set():
+                for k in self.samples:
+                    if k in self.files:
+                        v = self._read(self.files[k])
+                        if v is not None:
+                            self.samples[k].append(v)
+                self._stop.wait(self.period)
+        self._thread = threading.Thread(target=loop, daemon=True)
+        self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        self._thread.join()
+
+    def summary(self):
+        def mean(v):
+            return sum(v) / len(v) if v else None
+        p, c = self.samples["power_uw"], self.samples["sclk_hz"]
+        cap = self._read(self.files["cap_uw"]) if "cap_uw" in self.files else None
+        return {"power_w_mean": None if not p else mean(p) / 1e6, "power_w_max": None if not p else max(p) / 1e6,
+                "power_cap_w": None if cap is None else cap / 1e6,
+                "sclk_mhz_mean": None if not c else mean(c) / 1e6, "sclk_mhz_min": None if not c else min(c) / 1e6,
+                "samples": len(p) or len(c)}
+
+
+def bench_ceiling(args):
+    """Register-only MFMA rate on normally distributed and on all-zero operands, one and two
+    waves per SIMD: the measured ceiling beside the nominal 2.5 PFLOP/s."""
+    import torch
+    from paper_2111_04007_amd import binding as B, flops
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    props = torch.cuda.get_device_properties(dev)
+    gen = torch.Generator(device=dev).manual_seed(20211104)
+    n = 1 << 23
+    data = {"normal(0,1)": torch.empty(n, device=dev, dtype=torch.float32).normal_(generator=gen).to(torch.bfloat16),
+            "normal(0,0.02)": (torch.empty(n, device=dev, dtype=torch.float32).normal_(generator=gen) * 0.02).to(torch.bfloat16),
+            "zeros": torch.zeros(n, device=dev, dtype=torch.bfloat16)}
+    sink = torch.empty(props.multi_processor_count * 2 * 256, device=dev, dtype=torch.float32)
+    stream = torch.cuda.current_stream()
+    iters = 200000      # about 0.1 s per launch
+    rows = []
+    cases = [(name, wps, 0) for name in data for wps in (1, 2)] + [("normal(0,1)", 2, pat) for pat in (1, 2, 3)]
+    for name, wps, pat in cases:
+        t = data[name]
+        if True:
+            rates = []
+            sens = GpuSensors(0.01)
+            for rep in range(args.warmup + args.steps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                if rep == args.warmup:
+                    sens.__enter__()
+                e0.record(stream)
+                fl = B.probe_mfma_rate(t, wps, iters, sink, pat, stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                if rep >= args.warmup:
+                    rates.append(fl / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+            sens.__exit__()
+            rates.sort()
+            rows.append({"operands": name, "waves_per_simd": wps, "operand_pattern": pat, "tflops_median": rates[len(rates) // 2],
+                         "tflops_min": rates[0], "tflops_max": rates[-1],
+                         "frac_of_nominal_peak": rates[len(rates) // 2] * 1e12 / flops.MI355X_BF16_DENSE_PEAK,
+                         "implied_clock_mhz": rates[len(rates) // 2] * 1e12 / flops.MI355X_BF16_DENSE_PEAK * 2400.0,
+                         "sensors": sens.summary()})
+    best_real = max(r["tflops_median"] for r in rows if r["operands"] == "normal(0,1)" and r["operand_pattern"] == 0)
+    return {"metric": "register-only v_mfma_f32_32x32x16_bf16 rate (measured ceiling beside the nominal peak)",
+            "value": best_real, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "higher_is_better": True, "dtype": "bf16", "data": "synthetic", "vs_baseline": None,
+            "config": {"workload": "MFMA-only loop, no LDS or memory traffic", "device": props.name,
+                       "compute_units": props.multi_processor_count, "iters_per_launch": iters,
+                       "nominal_peak_tflops": flops.MI355X_BF16_DENSE_PEAK / 1e12},
+            "rows": rows}
 
 
 def main():
@@ -121,6 +233,9 @@ def main():
     if args.tail:
         print(json.dumps(bench_tail(cfg, args)))
         return
+    if args.ceiling:
+        print(json.dumps(bench_ceiling(args)))
+        return
     if args.micro_batches:
         cfg = cfg.replace(n_micro_batches=args.micro_batches)
     cfg = cfg.replace(wgrad_group=max(1, args.wgrad_group), dropout_p=args.dropout)
@@ -131,6 +246,7 @@ def main():
 
     params, xs, dys = synth.device_random_stage(cfg, dev)
     st = B.Stage(cfg, dev, params_flat=params)
+    st.set_side_stream(torch.cuda.Stream(dev))   # the caller's second stream for the bias-gradient sums
     if cfg.dropout_p > 0:
         st.set_dropout_seed(20211104)
     ys = torch.empty_like(xs)
@@ -156,13 +272,15 @@ def main():
         step()
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        marks[i].record(stream)     # per-step spread (median, min); the headline is the wall time of all steps
-        step()
-    marks[args.steps].record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    sensors = GpuSensors()
+    with sensors:
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            marks[i].record(stream)     # per-step spread (median, min); the headline is the wall time of all steps
+            step()
+        marks[args.steps].record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
     ms_step = wall * 1e3 / args.steps
     ms_mb = ms_step / M
     per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
@@ -253,13 +371,42 @@ def main():
                         "unit": "GB/s", "frac": ach / (flops.MI355X_HBM_PEAK / 1e9), "traffic": None,
                         "avg_launch_ms": v["ms"] / v["launches"], "launches": v["launches"] // args.steps}
 
-    # HBM traffic of the dominant kernel class from the committed rocprofv3 --pmc summary
+    # HBM traffic of the dominant kernel class: rocprofv3 --pmc counters cannot be read from inside
+    # this process, so the figure is the committed summary of two counter runs of this same command
+    # (profiles/hbm_traffic.json names the runs and the kernel sources they measured); null if that
+    # file has no entry for this workload and kernel class.
     if roofline is not None:
         try:
             with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
-                roofline["traffic"] = json.load(fh)[cfg.name][roofline["kernel"]]["hbm_bytes_per_launch"]
+                entry = json.load(fh)[cfg.name][roofline["kernel"]]
+            roofline["traffic"] = entry["hbm_bytes_per_launch"]
+            roofline["traffic_source"] = entry.get("source")
         except (OSError, KeyError, ValueError):
             roofline["traffic"] = None
+
+    # The same step with weight gradients accumulated after every micro-batch (wgrad_group = 1:
+    # no operand of a second micro-batch is ever held), reported beside the headline.
+    ungrouped = None
+    workspace_bytes = B.query_sizes(cfg)[3]
+    if cfg.wgrad_group > 1 and not args.no_ungrouped and not last:
+        cfg1 = cfg.replace(wgrad_group=1)
+        st.close()
+        del st
+        torch.cuda.empty_cache()
+        st = B.Stage(cfg1, dev, params_flat=params)
+        st.set_side_stream(torch.cuda.Stream(dev))
+        n1 = max(2, min(args.steps, 5))
+        step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(n1):
+            step()
+        torch.cuda.synchronize()
+        ms1 = (time.perf_counter() - t1) * 1e3 / n1
+        tf1 = hw_flops_mb * M / (ms1 * 1e-3) / 1e12
+        ungrouped = {"wgrad_group": 1, "steps": n1, "ms_per_step": ms1, "ms_per_micro_batch": ms1 / M, "tflops": tf1,
+                     "frac_of_bf16_mfma_peak": tf1 * 1e12 / flops.MI355X_BF16_DENSE_PEAK,
+                     "workspace_bytes": B.query_sizes(cfg1)[3]}
 
     cpu = None if args.no_cpu_baseline else cpu_baseline(cfg)
 
@@ -274,6 +421,8 @@ def main():
                         (f" with dropout {cfg.dropout_p}" if cfg.dropout_p > 0 else ""), "n_layers": cfg.n_layers, "hidden": cfg.hidden, "n_heads": cfg.n_heads,
             "seq_len": cfg.seq_len, "micro_batch": cfg.micro_batch, "n_micro_batches": M,
             "mlp_hidden": cfg.mlp_hidden, "causal": cfg.causal, "wgrad_group": cfg.wgrad_group, "dropout_p": cfg.dropout_p,
+            "workspace_bytes": workspace_bytes, "same_step_ungrouped": ungrouped,
+            "gpu_sensors_during_timed_steps": sensors.summary(),
             "ms_per_micro_batch": ms_mb, "ms_per_step_median": ms_step_median, "ms_per_step_min": ms_step_min,
             "ms_forward_per_micro_batch": ms_f,
             ("ms_backward_per_micro_batch" if last else "ms_recompute_backward_per_micro_batch"): ms_rb,

@@ -19,11 +19,11 @@
  *     device memory in any call.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *     Every compute call only enqueues work and returns; nothing synchronises
- *     with the host.  All results of a call are ordered on hip_stream: the
- *     backward calls run their bias-gradient reductions on a stream of the
- *     library's own (default priority, created at the first backward call),
- *     forked from and joined back into hip_stream with events inside the call.
- *     One handle is used from one stream at a time.
+ *     with the host.  All results of a call are ordered on hip_stream.  The
+ *     library creates no stream: if the caller hands over a second one with
+ *     varuna_stage_set_side_stream, the backward calls run their bias-gradient
+ *     reductions there, forked from and joined back into hip_stream with events
+ *     inside the call.  One handle is used from one stream at a time.
  *   - Activations are row-major [T, h], T = micro_batch * seq_len, row index
  *     = batch_index * seq_len + position.  dtype F32: all tensors fp32.
  *     dtype BF16: activations, parameters and dX are bf16; all accumulators,
@@ -83,7 +83,8 @@ typedef struct {
   int32_t dtype;           /* varuna_dtype_t */
   float ln_eps;            /* 0 means 1e-5 */
   int32_t wgrad_group;     /* G: weight-gradient GEMMs are issued once per G micro-batches with
-                              reduction length G*T (0 or 1: after every micro-batch) */
+                              reduction length G*T (0 or 1: after every micro-batch); on the bf16 path
+                              G * T * mlp_hidden * 2 bytes must stay below 4 GiB (VARUNA_EUNSUPPORTED) */
   float dropout_p;         /* dropout probability in [0,1), applied as round(256 p)/256; 0: none.
                               See varuna_stage_set_dropout_seed. */
 } varuna_stage_config_t;
@@ -144,6 +145,15 @@ varuna_status_t varuna_stage_forward_keep(varuna_stage_t* st, int32_t mb, const 
 varuna_status_t varuna_stage_backward_stored(varuna_stage_t* st, int32_t mb,
                                              const void* dy_in /*device*/,
                                              void* dx_out /*device*/, void* hip_stream);
+
+/* Optional second stream, created and owned by the caller (default priority; it must outlive
+ * the handle or be replaced by NULL first).  The bias-gradient column sums of the backward
+ * calls depend on nothing downstream of them and are bound by HBM, not by the matrix cores:
+ * given a side stream they overlap the GEMM chain; every backward call waits for them before
+ * it returns control of hip_stream's order, so the caller never has to synchronise with the
+ * side stream itself.  NULL (the state after create): everything runs on hip_stream.
+ * Results are bit-identical either way. */
+varuna_status_t varuna_stage_set_side_stream(varuna_stage_t* st, void* side_stream);
 
 /* Dropout (config.dropout_p > 0) acts on the attention probabilities and on the two residual
  * branches (attention-output projection and MLP output, after their bias, before the add).
@@ -227,6 +237,13 @@ varuna_status_t varuna_stage_debug_forward_save(varuna_stage_t* st, int32_t mb,
 varuna_status_t varuna_stage_debug_saved_region(const varuna_stage_t* st, size_t* offset_bytes,
                                                 size_t* n_bytes);
 
+/* Tuning aid: which bf16 MFMA GEMM kernel configuration (the `variant` numbers of varuna_op_gemm)
+ * the stage calls use for forward / dgrad / wgrad products on 256x256 and on 128x128 tiles; 0
+ * restores the library's choice.  Process-wide, not thread-safe, for same-process A/B timing
+ * only: results of every configuration agree to rounding but not bit for bit. */
+varuna_status_t varuna_debug_set_gemm_kernels(int32_t fwd256, int32_t dgrad256, int32_t wgrad256,
+                                              int32_t fwd128, int32_t dgrad128, int32_t wgrad128);
+
 /* ---- per-kernel timing (HIP events on the caller's stream) -------------- */
 
 /* Kernel classes reported by the profiler. */
@@ -251,6 +268,24 @@ varuna_status_t varuna_stage_profile_enable(varuna_stage_t* st, int32_t on);
  * then clears the record. */
 varuna_status_t varuna_stage_profile_collect(varuna_stage_t* st, double* ms, int64_t* launches,
                                              double* flops, double* bytes);
+
+/* ---- measurement hook: what the matrix cores sustain when fed from registers ----------
+ * Launches compute_units * waves_per_simd workgroups of 4 waves (waves_per_simd = 1 or 2),
+ * each wave issuing iters * 8 independent v_mfma_f32_32x32x16_bf16 products on operand
+ * fragments it loaded once from `operands` (device, bf16, n_elems a multiple of 8, 16-byte
+ * aligned; indices wrap) -- no LDS or memory traffic inside the loop.  pattern selects which
+ * of its 4 + 4 fragments consecutive products read: 0 both operands change every product,
+ * 1 the first is held for 8 products, 2 the first for 8 and the second for 2 (a 4x2 register
+ * tile walked row by row), 3 both always the same.  The caller times the
+ * launch with events on hip_stream; *flops (host, may be NULL) receives the floating-point
+ * operations of the launch.  sink: device, compute_units * waves_per_simd * 256 floats,
+ * receives accumulator sums (so the products cannot be elided).  The rate depends on the
+ * operand data (all-zero operands toggle no multiplier inputs and run at a higher clock
+ * than normally distributed ones): it is the measured ceiling a GEMM on the same kind of
+ * data sits under, reported beside the nominal peak. */
+varuna_status_t varuna_probe_mfma_rate(const void* operands /*device*/, int64_t n_elems, int32_t waves_per_simd,
+                                       int32_t pattern, int32_t iters, float* sink /*device*/,
+                                       double* flops /*host*/, void* hip_stream);
 
 /* ---- single-operation entry points (unit parity tests, kernel tuning) ---- */
 

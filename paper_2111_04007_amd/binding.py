@@ -27,11 +27,13 @@ OP_FWD, OP_DGRAD, OP_WGRAD = 0, 1, 2
 EXPORTS = (
     "varuna_stage_query_sizes", "varuna_stage_param_offset", "varuna_stage_create",
     "varuna_stage_forward", "varuna_stage_backward_recompute", "varuna_stage_grad_accum_reset",
-    "varuna_stage_forward_keep", "varuna_stage_backward_stored", "varuna_stage_grad_stats", "varuna_stage_adam_step", "varuna_stage_set_dropout_seed",
+    "varuna_stage_forward_keep", "varuna_stage_backward_stored", "varuna_stage_grad_stats", "varuna_stage_adam_step", "varuna_stage_set_dropout_seed", "varuna_stage_set_side_stream",
     "varuna_stage_grad_flush", "varuna_stage_destroy", "varuna_last_error", "varuna_stage_debug_forward_save",
     "varuna_stage_debug_saved_region", "varuna_stage_profile_enable", "varuna_stage_profile_collect",
     "varuna_op_gemm", "varuna_op_layernorm_fwd", "varuna_op_layernorm_bwd", "varuna_op_colsum",
     "varuna_op_colreduce_scratch_bytes", "varuna_op_attention_fwd", "varuna_op_attention_bwd",
+    "varuna_probe_mfma_rate",
+    "varuna_debug_set_gemm_kernels",
 )
 
 
@@ -83,6 +85,7 @@ def load():
         "varuna_stage_backward_stored": (i32, [vp, i32, vp, vp, vp]),
         "varuna_stage_grad_accum_reset": (i32, [vp, vp]),
         "varuna_stage_set_dropout_seed": (i32, [vp, C.c_uint64]),
+        "varuna_stage_set_side_stream": (i32, [vp, vp]),
         "varuna_stage_grad_stats": (i32, [vp, vp, vp]),
         "varuna_stage_adam_step": (i32, [vp, C.POINTER(CAdam), vp, vp, vp, vp, vp, vp]),
         "varuna_stage_grad_flush": (i32, [vp, vp]),
@@ -98,6 +101,8 @@ def load():
         "varuna_op_layernorm_bwd": (i32, [i32, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "varuna_op_colsum": (i32, [i32, i64, i64, vp, vp, vp, vp]),
         "varuna_op_colreduce_scratch_bytes": (sz, [i64, i64]),
+        "varuna_debug_set_gemm_kernels": (i32, [i32] * 6),
+        "varuna_probe_mfma_rate": (i32, [vp, i64, i32, i32, i32, vp, C.POINTER(C.c_double), vp]),
         "varuna_op_attention_fwd": (i32, [i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]),
         "varuna_op_attention_bwd": (i32, [i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
     }
@@ -199,6 +204,11 @@ class Stage:
     def backward_stored(self, mb: int, dy: torch.Tensor, dx: torch.Tensor, stream=None):
         _check(self.lib.varuna_stage_backward_stored(self.handle, mb, _ptr(dy), _ptr(dx), _stream_ptr(stream)))
 
+    def set_side_stream(self, stream):
+        """stream: a torch.cuda.Stream the caller keeps alive (held here too), or None."""
+        self._side_stream = stream
+        _check(self.lib.varuna_stage_set_side_stream(self.handle, None if stream is None else C.c_void_p(stream.cuda_stream)))
+
     def set_dropout_seed(self, seed: int):
         _check(self.lib.varuna_stage_set_dropout_seed(self.handle, seed))
 
@@ -281,6 +291,18 @@ def op_layernorm_bwd(dy, x, stats, gamma, res, dx, dgamma, dbeta, partial, strea
 def op_colsum(a, out, partial, stream=None):
     rows, n = a.shape
     _check(load().varuna_op_colsum(dtype_code(a), rows, n, _ptr(a), _ptr(out), _ptr(partial), _stream_ptr(stream)))
+
+
+def debug_set_gemm_kernels(fwd256=0, dgrad256=0, wgrad256=0, fwd128=0, dgrad128=0, wgrad128=0):
+    _check(load().varuna_debug_set_gemm_kernels(fwd256, dgrad256, wgrad256, fwd128, dgrad128, wgrad128))
+
+
+def probe_mfma_rate(operands, waves_per_simd: int, iters: int, sink, pattern: int = 0, stream=None) -> float:
+    """Enqueues the register-only MFMA loop; returns the FLOPs of the launch."""
+    fl = C.c_double()
+    _check(load().varuna_probe_mfma_rate(_ptr(operands), operands.numel(), waves_per_simd, pattern, iters, _ptr(sink),
+                                         C.byref(fl), _stream_ptr(stream)))
+    return fl.value
 
 
 def op_attention_fwd(qkv, ctx, lse, b, s, heads, d, causal, variant=0, stream=None):

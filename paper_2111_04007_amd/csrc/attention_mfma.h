@@ -597,6 +597,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+    // The products above are opaque to the compiler, which therefore adds no wait states
+    // between them and anything it may place around the loop's back-edge that reads dk / dv
+    // (a copy, a spill).  Settle once per tile: the accumulators are architecturally current
+    // at every point outside the run of products.
+    at_mfma_settle();
+    __builtin_amdgcn_sched_barrier(0);
   }
   at_mfma_settle();
   __builtin_amdgcn_sched_barrier(0);  // the reads of dK/dV below stay below the wait

@@ -18,11 +18,10 @@
 // Both give a lane the 8 consecutive k-values (lane/32)*8.. of tile row lane%32,
 // which is the operand layout of v_mfma_f32_32x32x16_bf16.
 #pragma once
-#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
-#include "gemm_mfma.h"  // mg_epilogue4, GemmOp
+#include "gemm_epilogue.h"
 
 namespace varuna {
 
@@ -80,6 +79,19 @@ struct DgLoader {
       const int q = wave + i * NW;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(lds_tile + q * 512), 16, voff[i], soff, 0, 0);
     }
+#endif
+  }
+  // Load number I of this wave alone.  With live == false the descriptor covers zero bytes: every
+  // lane is out of range, no memory request is made and the load only deposits zeros, so a
+  // k-tile past the end of the reduction costs no branch in the middle of a run of products.
+  template <int I>
+  __device__ __forceinline__ void issue_one(bf16* lds_tile, int kt, int wave, bool live) const {
+#if defined(__HIP_DEVICE_COMPILE__)
+    static_assert(I >= 0 && I < LPT, "load index");
+    const uint32_t soff = (uint32_t)kt * step;
+    const auto rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(base), 0, live ? extent : 0u, 0x00020000);
+    const int q = wave + I * NW;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(lds_tile + q * 512), 16, voff[I], live ? soff : 0u, 0, 0);
 #endif
   }
 };
@@ -153,7 +165,43 @@ struct DgInterleave {
   }
 };
 
-template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, int MODE>
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), unrolled at compile time.
+template <int N, typename F>
+__device__ __forceinline__ void dg_static_for(F&& f) {
+  if constexpr (N > 0) {
+    dg_static_for<N - 1>(f);
+    f(std::integral_constant<int, N - 1>{});
+  }
+}
+// A half-open range of load numbers handed to one k-step.
+template <int LO, int HI> struct DgLoads { static constexpr int lo = LO, hi = HI; };
+// Load number J (LO <= J < HI) goes out right after product number dg_load_slot of the k-step's NMFMA.
+constexpr int dg_load_slot(int j, int lo, int hi, int nmfma) { return ((j - lo) * nmfma) / (hi - lo); }
+constexpr uint32_t dg_load_mask(int lo, int hi, int nmfma) {
+  uint32_t m = 0;
+  for (int j = lo; j < hi; ++j) m |= 1u << dg_load_slot(j, lo, hi, nmfma);
+  return m;
+}
+// Scheduling hints for one k-step whose direct loads sit after the products named in VMASK.
+template <int Q, int NMFMA, int NREAD, int RPM, uint32_t VMASK>
+struct DgInterleaveMask {
+  static __device__ __forceinline__ void hint() {
+    if constexpr (Q < NMFMA) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if constexpr (Q * RPM < NREAD)
+        __builtin_amdgcn_sched_group_barrier(0x100, (Q * RPM + RPM <= NREAD) ? RPM : NREAD - Q * RPM, 0);
+      if constexpr ((VMASK >> Q) & 1u) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      DgInterleaveMask<Q + 1, NMFMA, NREAD, RPM, VMASK>::hint();
+    }
+  }
+};
+
+// LS (load schedule): 0 = the loads of a k-tile go out in one run right after the barrier that
+// frees their stage (from the upper half of the waves, or from both halves one k-step apart,
+// see below); 1 = every wave sends its share one load at a time between its products, spread
+// over the three k-steps that follow that barrier, so that no wave sits at the texture
+// addresser's full queue while its products wait.
+template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, int MODE, int LS = 0>
 __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
     const bf16* __restrict__ a, int64_t lda, const bf16* __restrict__ b, int64_t ldb, int K,
     int tiles_m, int tiles_n, EpiArgs<bf16> epi, int xcd_remap, int group) {
@@ -195,8 +243,8 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
   //     barrier, the upper half one k-step later.
   // With one wave per SIMD every wave sends its share right after the barrier.
   constexpr bool HAND = !(A_KMAJOR && B_KMAJOR);
-  constexpr bool SPLIT = (NW == 8) && HAND;          // two issue points
-  constexpr int NI = (NW == 8 && !HAND) ? 4 : NW;    // number of issuing waves
+  constexpr bool SPLIT = (NW == 8) && HAND && LS == 0;          // two issue points
+  constexpr int NI = (NW == 8 && !HAND && LS == 0) ? 4 : NW;    // number of issuing waves
   const bool issuer = wave >= NW - NI;
   const int iw = wave - (NW - NI);
   const bool early = !SPLIT || wave < NW / 2;
@@ -217,7 +265,34 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
   // gridDim.y splits of the reduction (EPI_STORE_F32 only): this workgroup owns k-tiles kt0 .. kt0+nk-1
   const int nk = K / DG_BK / (int)gridDim.y;
   const int kt0 = (int)blockIdx.y * nk;
-  if (issuer) {
+  // LDS map.  LS 0, 1: two stages of [A tile | B tile].  LS 2: two stages of A, then three of B.
+  constexpr int A_STRIDE = (LS == 2) ? BM * DG_BK : STAGE_ELEMS;
+  constexpr int B_STRIDE = (LS == 2) ? BN * DG_BK : STAGE_ELEMS;
+  constexpr int B_BASE = (LS == 2) ? 2 * BM * DG_BK : BM * DG_BK;
+  auto a_stage = [&](int i) { return smem + i * A_STRIDE; };
+  auto b_stage = [&](int i) { return smem + B_BASE + i * B_STRIDE; };
+  if constexpr (LS == 1) {
+    // tile 0 whole; of tile 1 only the loads that in the steady state go out right after a
+    // barrier -- the k-loop sends the rest during tile 0's first two k-steps, as for any tile
+    constexpr int LA1 = DgLoader<BM, NI, A_KMAJOR>::LPT, N31 = (LPT + 2) / 3;
+    la.issue(smem, kt0, iw);
+    lb.issue(smem + BM * DG_BK, kt0, iw);
+    dg_static_for<N31>([&](auto j_tag) {
+      constexpr int J = decltype(j_tag)::value;
+      if constexpr (J < LA1) la.template issue_one<J>(smem + STAGE_ELEMS, kt0 + 1, iw, nk > 1);
+      else lb.template issue_one<J - LA1>(smem + STAGE_ELEMS + BM * DG_BK, kt0 + 1, iw, nk > 1);
+    });
+    __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(N31));
+  } else if constexpr (LS == 2) {
+    // A(0), B(0) whole, then B(1) whole and the first half of A(1): what the steady state has sent
+    // for tile 0's barrier-to-barrier period by the time its k-step 0 starts.
+    constexpr int LA2 = DgLoader<BM, NI, A_KMAJOR>::LPT, LB2 = DgLoader<BN, NI, B_KMAJOR>::LPT;
+    la.issue(a_stage(0), kt0, iw);
+    lb.issue(b_stage(0), kt0, iw);
+    dg_static_for<LB2>([&](auto j_tag) { lb.template issue_one<decltype(j_tag)::value>(b_stage(1), kt0 + 1, iw, nk > 1); });
+    dg_static_for<LA2 / 2>([&](auto j_tag) { la.template issue_one<decltype(j_tag)::value>(a_stage(1), kt0 + 1, iw, nk > 1); });
+    __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LB2 + LA2 / 2));
+  } else if (issuer) {
     la.issue(smem, kt0, iw);
     lb.issue(smem + BM * DG_BK, kt0, iw);
     if (nk > 1) {
@@ -233,13 +308,17 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
   DgFragReg<A_KMAJOR, HAND> fa[2][TM];
   DgFragReg<B_KMAJOR, HAND> fb[2][TN];
 #pragma unroll
-  for (int j = 0; j < TN; ++j) DgFrag<BN, B_KMAJOR, HAND>::fetch(fb[0][j], smem + BM * DG_BK, wn * WN + j * 32, 0, lane);
+  for (int j = 0; j < TN; ++j) DgFrag<BN, B_KMAJOR, HAND>::fetch(fb[0][j], b_stage(0), wn * WN + j * 32, 0, lane);
 #pragma unroll
-  for (int i = 0; i < TM; ++i) DgFrag<BM, A_KMAJOR, HAND>::fetch(fa[0][i], smem, wm * WM + i * 32, 0, lane);
+  for (int i = 0; i < TM; ++i) DgFrag<BM, A_KMAJOR, HAND>::fetch(fa[0][i], a_stage(0), wm * WM + i * 32, 0, lane);
 
   constexpr int NMFMA = TM * TN;
   constexpr int NREAD = (A_KMAJOR ? TM : 2 * TM) + (B_KMAJOR ? TN : 2 * TN);
   constexpr int RPM = (NREAD + NMFMA - 1) / NMFMA;
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+
+  if constexpr (LS == 0) {
   // One k-step of 16: multiply fragment set `cur` while set `cur^1` is fetched from
   // (tile, ks_next).  The hints pin the order MFMA, LDS read, MFMA, LDS read, ... so the
   // LDS latency hides behind the matrix pipe.
@@ -266,8 +345,6 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
     if constexpr (!HAND) DgInterleave<0, NMFMA, NREAD, RPM, 0>::hint();
     else __builtin_amdgcn_sched_barrier(0);  // the products stay above the next k-step's wait
   };
-  using S0 = std::integral_constant<int, 0>;
-  using S1 = std::integral_constant<int, 1>;
 
   // Per k-tile kt (stage kt&1):
   //   k-steps 0..2 multiply while fetching the next k-step's fragments from the same tile;
@@ -293,6 +370,98 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
       lb.issue(cur + BM * DG_BK, kt0 + kt + 2, iw);
     }
     kstep(S1{}, nxt, 0);
+  }
+  } else {
+  // Loads sent one at a time between products.  A wave's LT loads of a k-tile are numbered A's
+  // first (LA of them), then B's.
+  //   LS 1: those numbered [0, N3) go out in the k-step after the barrier that frees their stage,
+  //     [N3, N3+N0) and the rest in the two k-steps after it; the k-step before the next barrier
+  //     carries none, so the last ones have that long to land.
+  //   LS 2: B has a third stage, so B's loads for tile kt+2 can go out while tile kt is still being
+  //     read: every k-step carries the same number of loads (A's halves in the k-step after the
+  //     barrier and the one after it, B's halves in the other two) and the path from L2 into LDS,
+  //     which is what bounds a 256x256 tile, never runs dry between barriers.
+  constexpr int LA = DgLoader<BM, NI, A_KMAJOR>::LPT, LB = DgLoader<BN, NI, B_KMAJOR>::LPT, LT = LPT;
+  static_assert(LS != 2 || (LA % 2 == 0 && LB % 2 == 0), "halves of each operand's loads");
+  constexpr int N3 = (LT + 2) / 3, N0 = (LT - N3 + 1) / 2;
+  auto kstep = [&](auto cur_tag, const bf16* ta, const bf16* tb, int ks_next, auto loads, bf16* lda_stage, int lda_kt,
+                   bool lda_live, bf16* ldb_stage, int ldb_kt, bool ldb_live) {
+    constexpr int cur = decltype(cur_tag)::value;
+    constexpr int LO = decltype(loads)::lo, HI = decltype(loads)::hi;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) dg_settle(fb[cur][j]);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) dg_settle(fa[cur][i]);
+    auto fetch_one = [&](auto r_tag) {   // read number r of the next k-step's fragments: B's first, then A's
+      constexpr int R = decltype(r_tag)::value;
+      if constexpr (R < TN) DgFrag<BN, B_KMAJOR, HAND>::fetch(fb[cur ^ 1][R], tb, wn * WN + R * 32, ks_next, lane);
+      else DgFrag<BM, A_KMAJOR, HAND>::fetch(fa[cur ^ 1][R - TN], ta, wm * WM + (R - TN) * 32, ks_next, lane);
+    };
+    if constexpr (HAND) {
+      dg_static_for<TM + TN>(fetch_one);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    dg_static_for<NMFMA>([&](auto q_tag) {
+      constexpr int Q = decltype(q_tag)::value, I = Q / TN, J = Q % TN;
+      acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dg_value(fb[cur][J]), dg_value(fa[cur][I]), acc[I][J], 0, 0, 0);
+      if constexpr (!HAND) {   // source order = the order the hints ask for: product, fragment read(s), load
+        constexpr int FR = (TM + TN + NMFMA - 1) / NMFMA;   // fragments per product
+        dg_static_for<FR>([&](auto f_tag) {
+          constexpr int R = Q * FR + decltype(f_tag)::value;
+          if constexpr (R < TM + TN) fetch_one(std::integral_constant<int, R>{});
+        });
+      }
+      if constexpr (HI > LO) {
+        dg_static_for<HI - LO>([&](auto l_tag) {
+          constexpr int L = LO + decltype(l_tag)::value;
+          if constexpr (dg_load_slot(L, LO, HI, NMFMA) == Q) {
+            if constexpr (HAND) __builtin_amdgcn_sched_barrier(0);
+            if constexpr (L < LA) la.template issue_one<L>(lda_stage, lda_kt, iw, lda_live);
+            else lb.template issue_one<L - LA>(ldb_stage, ldb_kt, iw, ldb_live);
+            if constexpr (HAND) __builtin_amdgcn_sched_barrier(0);
+          }
+        });
+      }
+    });
+    if constexpr (!HAND) DgInterleaveMask<0, NMFMA, NREAD, RPM, (HI > LO ? dg_load_mask(LO, HI, NMFMA) : 0u)>::hint();
+    else __builtin_amdgcn_sched_barrier(0);
+  };
+  if constexpr (LS == 1) {
+    for (int kt = 0; kt < nk; ++kt) {
+      bf16* cur = smem + (kt & 1) * STAGE_ELEMS;
+      bf16* nxt = smem + ((kt & 1) ^ 1) * STAGE_ELEMS;
+      bf16* curb = cur + BM * DG_BK;
+      bf16* nxtb = nxt + BM * DG_BK;
+      // A load for a k-tile past the end deposits zeros into a stage nobody reads any more.
+      const bool live_next = kt + 1 < nk;   // tile kt+1's remaining loads
+      kstep(S0{}, cur, curb, 1, DgLoads<N3, N3 + N0>{}, nxt, kt0 + kt + 1, live_next, nxtb, kt0 + kt + 1, live_next);
+      kstep(S1{}, cur, curb, 2, DgLoads<N3 + N0, LT>{}, nxt, kt0 + kt + 1, live_next, nxtb, kt0 + kt + 1, live_next);
+      kstep(S0{}, cur, curb, 3, DgLoads<0, 0>{}, nxt, 0, false, nxtb, 0, false);
+      __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
+      __builtin_amdgcn_s_barrier();
+      kstep(S1{}, nxt, nxtb, 0, DgLoads<0, N3>{}, cur, kt0 + kt + 2, kt + 2 < nk, curb, kt0 + kt + 2, kt + 2 < nk);
+    }
+  } else {
+    int bs = 0;   // B stage of tile kt (kt mod 3)
+    for (int kt = 0; kt < nk; ++kt) {
+      bf16* ca = a_stage(kt & 1);
+      bf16* na = a_stage((kt & 1) ^ 1);
+      const int bs1 = bs == 2 ? 0 : bs + 1, bs2 = bs1 == 2 ? 0 : bs1 + 1;
+      bf16* cb = b_stage(bs);
+      bf16* nb = b_stage(bs1);
+      bf16* nnb = b_stage(bs2);   // held tile kt-1: free since the last barrier
+      const bool live1 = kt + 1 < nk, live2 = kt + 2 < nk;
+      kstep(S0{}, ca, cb, 1, DgLoads<LA / 2, LA>{}, na, kt0 + kt + 1, live1, nnb, 0, false);
+      kstep(S1{}, ca, cb, 2, DgLoads<LA, LA + LB / 2>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
+      kstep(S0{}, ca, cb, 3, DgLoads<LA + LB / 2, LT>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
+      // tile kt+1 has landed (A's second half went out three k-steps ago, B's a period ago); the
+      // LB loads of B(kt+2) sent since then may still be in flight
+      __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LB) & DG_WAIT_LGKM0);
+      __builtin_amdgcn_s_barrier();
+      kstep(S1{}, na, nb, 0, DgLoads<0, LA / 2>{}, ca, kt0 + kt + 2, live2, nnb, 0, false);
+      bs = bs1;
+    }
+  }
   }
 
   const int frow = lane & 31, fchunk = lane >> 5;
@@ -383,7 +552,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
         const floatx4 lo = *reinterpret_cast<const floatx4*>(buf + r * ROWB + (((c0 & ~15) | ((c0 ^ r) & 15)) << 4));
         const floatx4 hi = *reinterpret_cast<const floatx4*>(buf + r * ROWB + ((((c0 + 1) & ~15) | (((c0 + 1) ^ r) & 15)) << 4));
         float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        mg_epilogue8<MODE>(epi, m0 + wm * WM + i * 32 + r, n0 + wn * WN + rcol, v);
+        gemm_epilogue8<MODE>(epi, m0 + wm * WM + i * 32 + r, n0 + wn * WN + rcol, v);
       }
       __builtin_amdgcn_s_waitcnt(DG_WAIT_LGKM0);  // reads done before the next pass overwrites
     }
@@ -391,20 +560,22 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// host side.  Variant ids continue the first-generation kernel's (1..4):
+// host side.  Variant ids (0 is "the library's choice", -1 the plain FMA kernel):
 //   5: 256x256 tile, 8 waves   6: 256x256, 4 waves   7: 128x128, 4 waves   8: 256x128, 4 waves
+//   9: as 5 with the spread load schedule   10: as 7 with the spread load schedule   11: as 6 with it
+//   12: as 5 with three stages of B and loads in every k-step   13: as 6 with that   14: as 7 with that
 // ---------------------------------------------------------------------------
-inline bool dg_variant_tile(int variant, MgTile* t) {
+inline bool dg_variant_tile(int variant, GemmTile* t) {
   switch (variant) {
-    case 5: case 6: *t = {256, 256}; return true;
-    case 7: *t = {128, 128}; return true;
+    case 5: case 6: case 9: case 11: case 12: case 13: *t = {256, 256}; return true;
+    case 7: case 10: case 14: *t = {128, 128}; return true;
     case 8: *t = {256, 128}; return true;
     default: return false;
   }
 }
 
 inline bool dg_shape_ok(int variant, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb) {
-  MgTile t;
+  GemmTile t;
   if (!dg_variant_tile(variant, &t)) return false;
   // operands are addressed with 32-bit byte offsets from their base (buffer loads)
   const int64_t a_bytes = (M > K ? M : K) * lda * 2, b_bytes = (N > K ? N : K) * ldb * 2;
@@ -424,27 +595,31 @@ inline int dg_choose_variant(int64_t M, int64_t N, int64_t K, int64_t lda, int64
   return cost5 <= cost7 ? 5 : 7;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AK, bool BK_, int MODE>
+// Kernel configuration for a product once the tile size is chosen (tile_variant 5: 256x256, 7:
+// 128x128), as measured on normally distributed operands at the stage shapes: the 256x256 forward
+// product runs best on 4 waves (128x128 per wave: a third fewer LDS reads per product) with the
+// loads sent in every k-step; the products with a transposing operand keep 8 waves (two per SIMD
+// hide each other's waits on the two-instruction transposed reads) with the same load schedule.
+struct DgFlavours { int fwd256 = 13, bwd256 = 12, fwd128 = 14, dgrad128 = 14, wgrad128 = 7, wgrad256 = 12; };
+inline DgFlavours& dg_flavours() { static DgFlavours f; return f; }   // tuning hook: varuna_debug_set_gemm_kernels
+inline int dg_flavour(int tile_variant, int op) {
+  const DgFlavours& f = dg_flavours();
+  if (tile_variant == 5) return op == GEMM_FWD ? f.fwd256 : (op == GEMM_DGRAD ? f.bwd256 : f.wgrad256);
+  if (tile_variant == 7) return op == GEMM_FWD ? f.fwd128 : (op == GEMM_DGRAD ? f.dgrad128 : f.wgrad128);
+  return tile_variant;
+}
+
+template <int BM, int BN, int WGM, int WGN, bool AK, bool BK_, int MODE, int LS = 0>
 inline hipError_t dg_launch_one(const bf16* a, int64_t lda, const bf16* b, int64_t ldb, int64_t M, int64_t N,
                                 int64_t K, const EpiArgs<bf16>& epi, int splits, hipStream_t st) {
-  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, AK, BK_, MODE>;
-  constexpr size_t smem = (size_t)DG_STAGES * (BM + BN) * DG_BK * sizeof(bf16);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, AK, BK_, MODE, LS>;
+  constexpr size_t smem = (size_t)(LS == 2 ? 2 * BM + 3 * BN : DG_STAGES * (BM + BN)) * DG_BK * sizeof(bf16);
+  // the first call raises the kernel's dynamic LDS limit (thread-safe: initialisation of a local static)
+  static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (attr_err != hipSuccess) return attr_err;
   const int tm = (int)(M / BM), tn = (int)(N / BN);
-  static int xcd_remap = -1, group = 8;
-  if (xcd_remap < 0) {  // tuning knobs
-    const char* e1 = getenv("VARUNA_XCD_REMAP");
-    const char* e2 = getenv("VARUNA_TILE_GROUP");
-    xcd_remap = e1 ? atoi(e1) : 1;
-    group = e2 ? atoi(e2) : 8;
-    if (group < 1) group = 1;
-  }
+  constexpr int xcd_remap = 1, group = 8;   // tile order: contiguous range per XCD, walked in groups of 8 tile rows
   if (splits < 1 || (MODE != EPI_STORE_F32 && splits != 1) || (K / DG_BK) % splits != 0) return hipErrorInvalidValue;
   hipLaunchKernelGGL(kern, dim3((unsigned)(tm * tn), (unsigned)splits), dim3(WGM * WGN * kWave), smem, st, a, lda, b, ldb,
                      (int)K, tm, tn, epi, xcd_remap, group);
@@ -459,6 +634,12 @@ inline hipError_t dg_launch_variant(int variant, const bf16* a, int64_t lda, con
     case 6: return dg_launch_one<256, 256, 2, 2, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, splits, st);
     case 7: return dg_launch_one<128, 128, 2, 2, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, splits, st);
     case 8: return dg_launch_one<256, 128, 2, 2, AK, BK_, MODE>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 9: return dg_launch_one<256, 256, 2, 4, AK, BK_, MODE, 1>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 10: return dg_launch_one<128, 128, 2, 2, AK, BK_, MODE, 1>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 11: return dg_launch_one<256, 256, 2, 2, AK, BK_, MODE, 1>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 12: return dg_launch_one<256, 256, 2, 4, AK, BK_, MODE, 2>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 13: return dg_launch_one<256, 256, 2, 2, AK, BK_, MODE, 2>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 14: return dg_launch_one<128, 128, 2, 2, AK, BK_, MODE, 2>(a, lda, b, ldb, M, N, K, epi, splits, st);
     default: return hipErrorInvalidValue;
   }
 }
@@ -469,7 +650,7 @@ inline hipError_t dg_launch_variant(int variant, const bf16* a, int64_t lda, con
 // fixed order, so the result stays run-to-run deterministic.  Returns 1 when no split pays.
 inline int dg_wgrad_splits(int64_t M, int64_t N, int64_t K) {
   const int v = dg_choose_variant(M, N, K, M, N);
-  MgTile t;
+  GemmTile t;
   if (v == 0 || !dg_variant_tile(v, &t)) return 1;
   const int64_t tiles = (M / t.bm) * (N / t.bn), slots = (v == 5) ? 256 : 512, nk = K / DG_BK;
   int64_t s = slots / tiles;

@@ -1,0 +1,52 @@
+// Measurement hook: the rate the matrix cores sustain on v_mfma_f32_32x32x16_bf16 when fed
+// from registers only (no LDS, no memory traffic in the loop).  It is the ceiling any GEMM
+// on this chip sits under for a given kind of operand data: the clock the chip holds depends
+// on how many operand bits toggle, so all-zero operands and normally distributed operands
+// give different rates.  Not on the stage's path.
+#pragma once
+#include "common.h"
+
+namespace varuna {
+
+// Every wave loads 4 + 4 operand fragments (8 bf16 per lane each) from `src` (n_vec 16-byte
+// vectors, indices wrap) once, then issues iters x 8 independent products into 8 accumulator
+// tiles and writes the sum of its accumulators so that the work cannot be dropped.
+// PATTERN selects which fragments consecutive products read (the data is the same in all):
+//   0: both operands change from one product to the next;
+//   1: the first operand is held for 8 consecutive products, the second changes every time;
+//   2: the first is held for 8, the second for 2 (the order a 4x2 register tile walked row by row gives);
+//   3: both operands are the same fragments for every product.
+template <int PATTERN>
+__global__ __launch_bounds__(256) void mfma_rate_kernel(const bf16x8* __restrict__ src, uint32_t n_vec,
+                                                        float* __restrict__ sink, int iters) {
+  floatx16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  bf16x8 a[4], b[4];
+  const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a[i] = src[(gid * 8u + i) % n_vec];
+    b[i] = src[(gid * 8u + 4u + i) % n_vec];
+  }
+  for (int it = 0; it < iters; it += 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int ia = PATTERN == 0 ? (i & 3) : (PATTERN == 3 ? 0 : u);
+        const int ib = PATTERN == 0 ? ((i + u) & 3) : (PATTERN == 1 ? (i & 3) : (PATTERN == 2 ? ((i >> 1) & 3) : 0));
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ia], b[ib], acc[i], 0, 0, 0);
+      }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  sink[gid] = s;
+}
+
+}  // namespace varuna

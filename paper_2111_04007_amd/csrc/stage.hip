@@ -28,8 +28,8 @@
 #include "attention_simple.h"
 #include "common.h"
 #include "gemm_dma.h"
-#include "gemm_mfma.h"
 #include "gemm_simple.h"
+#include "mfma_probe.h"
 #include "norm_reduce.h"
 #include "optimizer.h"
 
@@ -81,6 +81,11 @@ varuna_status_t make_dims(const varuna_stage_config_t* c, Dims* o) {
   o->causal = c->causal; o->dtype = c->dtype;
   if (c->wgrad_group < 0 || c->wgrad_group > 64) return fail(VARUNA_EINVAL, "wgrad_group must be in [0, 64]");
   o->G = c->wgrad_group > 1 ? c->wgrad_group : 1;
+  // the MFMA GEMMs address an operand with 32-bit byte offsets: a stacked ring of G slots must stay below 4 GiB
+  if (c->dtype == VARUNA_BF16 && o->G > 1 &&
+      (int64_t)o->G * c->micro_batch * c->seq_len * (int64_t)(c->mlp_hidden ? c->mlp_hidden : 4 * c->hidden) * 2 >= (1ll << 32))
+    return fail(VARUNA_EUNSUPPORTED, "wgrad_group %d: %d stacked micro-batches of the [tokens, mlp_hidden] operand reach 4 GiB",
+                c->wgrad_group, o->G);
   o->eps = c->ln_eps > 0.0f ? c->ln_eps : 1e-5f;
   o->T = (int64_t)o->b * o->s; o->E = o->T * o->h; o->F = o->T * o->f;
   o->es = c->dtype == VARUNA_F32 ? 4 : 2;
@@ -199,8 +204,9 @@ struct varuna_stage {
   int kept_slot = 0; // ring slot they were written to
   uint64_t seed = 0;  // dropout seed (varuna_stage_set_dropout_seed)
   // The bias-gradient column sums of the backward pass depend on nothing downstream and are
-  // HBM-bound, so they run on a stream of the library's own beside the GEMM chain (forked and
-  // joined with events inside every backward call; created at the first backward call).
+  // HBM-bound: when the caller has handed over a second stream (varuna_stage_set_side_stream)
+  // they run there beside the GEMM chain, forked and joined with events inside every backward
+  // call; otherwise on the caller's stream, in order.
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   bool side_used = false;  // work was forked in the current call and has not been joined yet
@@ -259,19 +265,14 @@ template <> struct GemmDispatch<bf16> {
                         aligned16(e.out) && aligned16(e.aux_out) && aligned16(e.out_f32) && (N % 8 == 0);
     int v = variant;
     if (v == 0) {
-      v = ptr_ok ? dg_choose_variant(M, N, K, lda, ldb) : -1;
-      if (v == 0) v = mg_choose_variant(M, N, K, lda, ldb);
+      v = ptr_ok ? dg_flavour(dg_choose_variant(M, N, K, lda, ldb), op) : -1;
       if (v == 0) v = -1;
     }
     if (v >= 5) {
       if (!ptr_ok || !dg_shape_ok(v, M, N, K, lda, ldb)) return hipErrorInvalidConfiguration;
       return launch_gemm_dma(op, mode, v, a, lda, b, ldb, M, N, K, e, s, splits);
     }
-    if (splits != 1) return hipErrorInvalidConfiguration;
-    if (v > 0) {
-      if (!ptr_ok || !mg_shape_ok(v, M, N, K, lda, ldb)) return hipErrorInvalidConfiguration;
-      return launch_gemm_mfma(op, mode, v, a, lda, b, ldb, M, N, K, e, s);
-    }
+    if (splits != 1 || v != -1) return hipErrorInvalidConfiguration;
     if (op == GEMM_FWD) return launch_gemm_simple<bf16>(mode, a, K, 1, b, K, 1, M, N, K, e, s);
     if (op == GEMM_DGRAD) return launch_gemm_simple<bf16>(mode, a, K, 1, b, 1, N, M, N, K, e, s);
     return launch_gemm_simple<bf16>(mode, a, 1, M, b, 1, N, M, N, K, e, s);
@@ -391,14 +392,6 @@ struct StageOps {
     return launch_colsum<T>(a, out, wsp<float>(S->ws.partial_side), D.T, n, S->side);
   }
 
-  // Creates the side stream on first use (no GPU call happens at stage creation).
-  hipError_t ensure_side() {
-    if (S->side != nullptr) return hipSuccess;
-    hipError_t e;
-    if ((e = hipStreamCreateWithFlags(&S->side, hipStreamNonBlocking))) return e;
-    if ((e = hipEventCreateWithFlags(&S->ev_fork, hipEventDisableTiming))) return e;
-    return hipEventCreateWithFlags(&S->ev_join, hipEventDisableTiming);
-  }
   // The caller's stream waits for everything forked since the last join.
   hipError_t join_side() {
     if (!S->side_used) return hipSuccess;
@@ -550,7 +543,6 @@ struct StageOps {
   hipError_t backward(int mb, const T* dy_in, T* dx_out, bool recompute_first) {
     hipError_t e;
     const int rs = S->pending;
-    if ((e = ensure_side())) return e;
     if (recompute_first && (e = recompute(mb, nullptr, rs))) return e;
     {  // the upstream gradient joins the top layer's dy ring
       Bracket br(S, st, VARUNA_K_OTHER, 0, 2.0 * D.E * sizeof(T));
@@ -674,13 +666,19 @@ varuna_status_t varuna_stage_create(const varuna_stage_config_t* cfg, const void
 varuna_status_t varuna_stage_destroy(varuna_stage_t* st) {
   if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
   for (hipEvent_t e : st->ev) (void)hipEventDestroy(e);
-  if (st->side) {
-    (void)hipStreamSynchronize(st->side);
-    (void)hipStreamDestroy(st->side);
-    (void)hipEventDestroy(st->ev_fork);
-    (void)hipEventDestroy(st->ev_join);
-  }
+  if (st->ev_fork) (void)hipEventDestroy(st->ev_fork);   // the side stream itself is the caller's
+  if (st->ev_join) (void)hipEventDestroy(st->ev_join);
   delete st;
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_stage_set_side_stream(varuna_stage_t* st, void* side_stream) {
+  if (!st) return fail(VARUNA_EINVAL, "stage handle is NULL");
+  if (side_stream && !st->ev_fork) {
+    HIP_TRY(hipEventCreateWithFlags(&st->ev_fork, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&st->ev_join, hipEventDisableTiming));
+  }
+  st->side = static_cast<hipStream_t>(side_stream);
   return VARUNA_OK;
 }
 
@@ -919,6 +917,48 @@ varuna_status_t varuna_op_colsum(int32_t dtype, int64_t rows, int64_t n, const v
   else if (dtype == VARUNA_BF16) e = launch_colsum<bf16>(static_cast<const bf16*>(a), out_f32, partial_f32, rows, n, s);
   else return fail(VARUNA_EINVAL, "unknown dtype %d", dtype);
   return hip_result(e, "varuna_op_colsum");
+}
+
+varuna_status_t varuna_debug_set_gemm_kernels(int32_t fwd256, int32_t dgrad256, int32_t wgrad256, int32_t fwd128,
+                                              int32_t dgrad128, int32_t wgrad128) {
+  const int32_t v[6] = {fwd256, dgrad256, wgrad256, fwd128, dgrad128, wgrad128};
+  GemmTile t;
+  for (int i = 0; i < 6; ++i) {
+    if (v[i] == 0) continue;
+    if (!dg_variant_tile(v[i], &t) || t.bm != t.bn || t.bm != (i < 3 ? 256 : 128))
+      return fail(VARUNA_EINVAL, "kernel configuration %d does not exist or has another tile size", v[i]);
+  }
+  const DgFlavours d;
+  DgFlavours& f = dg_flavours();
+  f.fwd256 = fwd256 ? fwd256 : d.fwd256; f.bwd256 = dgrad256 ? dgrad256 : d.bwd256; f.wgrad256 = wgrad256 ? wgrad256 : d.wgrad256;
+  f.fwd128 = fwd128 ? fwd128 : d.fwd128; f.dgrad128 = dgrad128 ? dgrad128 : d.dgrad128; f.wgrad128 = wgrad128 ? wgrad128 : d.wgrad128;
+  return VARUNA_OK;
+}
+
+varuna_status_t varuna_probe_mfma_rate(const void* operands, int64_t n_elems, int32_t waves_per_simd, int32_t pattern,
+                                       int32_t iters, float* sink, double* flops, void* hip_stream) {
+  if (pattern < 0 || pattern > 3) return fail(VARUNA_EINVAL, "pattern must be in [0, 3]");
+  if (!operands || !sink) return fail(VARUNA_EINVAL, "NULL pointer");
+  if (n_elems < 8 || n_elems > (1ll << 31) || n_elems % 8 != 0) return fail(VARUNA_EINVAL, "n_elems must be a multiple of 8 in [8, 2^31]");
+  if (reinterpret_cast<uintptr_t>(operands) % 16 != 0) return fail(VARUNA_EINVAL, "operands must be 16-byte aligned");
+  if (waves_per_simd < 1 || waves_per_simd > 2) return fail(VARUNA_EINVAL, "waves_per_simd must be 1 or 2");
+  if (iters < 4 || iters % 4 != 0 || iters > (1 << 24)) return fail(VARUNA_EINVAL, "iters must be a multiple of 4 in [4, 2^24]");
+  int dev = 0, cus = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  if (cus < 1 || cus > 1024) return fail(VARUNA_EHIP, "implausible compute-unit count %d", cus);
+  const unsigned nwg = (unsigned)(cus * waves_per_simd);   // 4 waves per workgroup: one per SIMD
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const bf16x8* src = static_cast<const bf16x8*>(operands);
+  const uint32_t nv = (uint32_t)(n_elems / 8);
+  switch (pattern) {
+    case 0: hipLaunchKernelGGL(mfma_rate_kernel<0>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
+    case 1: hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
+    case 2: hipLaunchKernelGGL(mfma_rate_kernel<2>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
+    default: hipLaunchKernelGGL(mfma_rate_kernel<3>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
+  }
+  if (flops) *flops = (double)nwg * 4.0 * (double)iters * 8.0 * (2.0 * 32 * 32 * 16);
+  return hip_result(hipGetLastError(), "varuna_probe_mfma_rate");
 }
 
 static varuna_status_t check_attn(int32_t b, int32_t s, int32_t heads, int32_t d) {

@@ -135,3 +135,12 @@ def test_pick_micro_batch_rule():
     assert pick_micro_batch(ms, [4.0, 3.0, 3.2, 2.5, 2.49]) == 8           # a non-monotone bump does not stop the search
     with pytest.raises(ValueError):
         pick_micro_batch([], [])
+
+
+def test_grouped_rings_must_stay_addressable_with_32_bit_offsets():
+    """bf16 path: G stacked micro-batches of the [T, f] weight-gradient operand must stay
+    below 4 GiB (config 5: 128 MiB per slot, so G = 32 is the first group size refused)."""
+    c5 = CONFIGS["C5"]
+    assert B.query_sizes(c5.replace(wgrad_group=31))[3] > 0
+    _expect(B.EUNSUPPORTED, B.query_sizes, c5.replace(wgrad_group=32))
+    assert B.query_sizes(CONFIGS["C1"].replace(wgrad_group=64))[3] > 0

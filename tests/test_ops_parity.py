@@ -69,10 +69,14 @@ def test_gemm_bf16_simple_kernel(shape):
 
 
 @pytest.mark.parametrize("variant,shape", [
-    (1, (512, 768, 256)), (2, (512, 768, 256)), (3, (512, 384, 192)), (4, (384, 640, 320)),
-    (2, (256, 256, 64)), (4, (128, 128, 64)),
     (5, (512, 768, 256)), (6, (512, 768, 256)), (7, (384, 640, 320)), (8, (512, 384, 192)),
     (5, (256, 256, 64)), (7, (128, 128, 64)), (7, (256, 128, 128)), (6, (256, 512, 192)),
+    (9, (512, 768, 256)), (9, (256, 256, 64)), (9, (256, 512, 128)), (9, (512, 256, 448)),
+    (10, (384, 640, 320)), (10, (128, 128, 64)), (10, (256, 128, 192)),
+    (11, (512, 768, 256)), (11, (256, 256, 64)),
+    (12, (512, 768, 256)), (12, (256, 256, 64)), (12, (256, 512, 128)), (12, (512, 256, 448)),
+    (13, (512, 768, 256)), (13, (256, 256, 64)), (13, (256, 512, 192)),
+    (14, (384, 640, 320)), (14, (128, 128, 64)), (14, (256, 128, 192)),
 ])
 def test_gemm_bf16_mfma_variants(variant, shape):
     """Each MFMA tile configuration on several tiles, k-steps and a single-k-step case."""
@@ -85,7 +89,7 @@ def test_gemm_bf16_auto_choice_and_unsupported_variant():
     w = rnd((128, 64), "bf16", 2)
     out = torch.empty((100, 128), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(B.VarunaError) as ei:
-        B.op_gemm(B.OP_FWD, 0, a, w, out, bias=w[0].contiguous(), variant=4, M=100, N=128, K=64)
+        B.op_gemm(B.OP_FWD, 0, a, w, out, bias=w[0].contiguous(), variant=7, M=100, N=128, K=64)
     assert ei.value.code == B.EUNSUPPORTED
 
 

@@ -107,3 +107,51 @@ def test_adam_skip_flag_and_pending_gradients():
     assert ei.value.code == B.EINVAL
     torch.cuda.synchronize()
     st.close()
+
+
+def test_tail_at_the_largest_stage_size():
+    """Gradient statistics and one Adam step over the 1.6 G parameters of config 5 (the size
+    the tail is timed on: 64-bit indexing, grid-stride loops over 6.4 GB buffers).  The sum of
+    squares and the non-finite count are compared over ALL entries (the oracle runs over host
+    chunks); the Adam update is compared on sampled windows of 2^20 entries -- the first, the
+    last, and 14 seeded ones in between -- and the rounded parameters on every entry."""
+    cfg = CONFIGS["C5"].replace(n_micro_batches=1, wgrad_group=1)
+    dev = "cuda:0"
+    params, _, _ = synth.device_random_stage(cfg, dev, 1)
+    st = B.Stage(cfg, dev, params_flat=params)
+    n = st.grads.numel()
+    assert n > (1 << 30)
+    gen = torch.Generator(device=dev).manual_seed(77)
+    st.grads.normal_(0.0, 2.0, generator=gen)
+    planted = [5, n // 3, n - 1]
+    for i, v in zip(planted, (float("nan"), float("inf"), float("-inf"))):
+        st.grads[i] = v
+    out = torch.zeros(2, device=dev)
+    st.grad_stats(out)
+    chunk = 1 << 26
+    ref_sumsq, ref_bad = T.grad_stats([st.grads[o:o + chunk].cpu().numpy() for o in range(0, n, chunk)])
+    got = out.cpu().numpy()
+    assert ref_bad == 3 and got[1] == 3.0
+    assert abs(float(got[0]) - ref_sumsq) <= 1e-6 * ref_sumsq, (got[0], ref_sumsq)
+    for i in planted:
+        st.grads[i] = 0.25
+
+    win = 1 << 20
+    rng = np.random.Generator(np.random.Philox(key=[5, 2111]))
+    starts = [0, n - win] + [int(o) for o in rng.integers(win, n - 2 * win, size=14)]
+    master = st.params.to(torch.float32)
+    m = torch.empty(n, device=dev).normal_(0.0, 0.1, generator=gen)
+    v = torch.empty(n, device=dev).uniform_(0.0, 0.5, generator=gen)
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.01, grad_scale=1.0 / 32)
+    before = [(o, master[o:o + win].cpu().double().numpy(), m[o:o + win].cpu().double().numpy(),
+               v[o:o + win].cpu().double().numpy(), st.grads[o:o + win].cpu().double().numpy()) for o in starts]
+    st.adam_step(master, m, v, 3, **hp)
+    torch.cuda.synchronize()
+    for o, w0, m0, v0, g0 in before:
+        w1, m1, v1 = T.adam_step(w0, m0, v0, g0, 3, **hp)
+        for got_t, ref, what in ((master, w1, "master"), (m, m1, "m"), (v, v1, "v")):
+            g_ = got_t[o:o + win].cpu().double().numpy()
+            err = np.linalg.norm(g_ - ref) / np.linalg.norm(ref)
+            assert err <= 1e-6, (what, o, err)
+    assert torch.equal(st.params, master.to(st.params.dtype))
+    st.close()

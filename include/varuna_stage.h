@@ -319,6 +319,21 @@ varuna_status_t varuna_op_colsum(int32_t dtype, int64_t rows, int64_t n, const v
                                  float* out_f32, float* partial_f32, void* hip_stream);
 size_t varuna_op_colreduce_scratch_bytes(int64_t rows, int64_t n);
 
+/* varuna_op_colsum for callers that cannot allocate device memory and have no workspace to
+ * hand over (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the stage-1 partial sums go to a device array built into the library
+ * (varuna_op_colsum_static_max_bytes() = 4 MiB per GPU, held until the process ends), so the
+ * call takes inputs and outputs only and calls no allocating routine.  Same kernels, same
+ * result bit for bit as varuna_op_colsum.  Shapes whose partial sums
+ * (varuna_op_colreduce_scratch_bytes(rows, n)) exceed the built-in array are rejected with
+ * VARUNA_EUNSUPPORTED before anything is enqueued.  All calls on one GPU share that array:
+ * calls whose kernels may overlap on the GPU (different streams, no ordering between them)
+ * race; calls ordered on one stream do not.  The array's address is looked up once per
+ * device at the first call on that device (the current device when the call is made). */
+varuna_status_t varuna_op_colsum_static(int32_t dtype, int64_t rows, int64_t n, const void* a /*device*/,
+                                        float* out_f32 /*device*/, void* hip_stream);
+size_t varuna_op_colsum_static_max_bytes(void);
+
 /* Attention forward on qkv [b*s, 3h] -> ctx [b*s, h], lse_f32 [b, heads, s]. */
 varuna_status_t varuna_op_attention_fwd(int32_t dtype, int32_t variant, int32_t b, int32_t s,
                                         int32_t heads, int32_t d, int32_t causal, const void* qkv,

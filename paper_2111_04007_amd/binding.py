@@ -32,7 +32,7 @@ EXPORTS = (
     "varuna_stage_debug_saved_region", "varuna_stage_profile_enable", "varuna_stage_profile_collect",
     "varuna_op_gemm", "varuna_op_layernorm_fwd", "varuna_op_layernorm_bwd", "varuna_op_colsum",
     "varuna_op_colreduce_scratch_bytes", "varuna_op_attention_fwd", "varuna_op_attention_bwd",
-    "varuna_probe_mfma_rate",
+    "varuna_op_colsum_static", "varuna_op_colsum_static_max_bytes", "varuna_probe_mfma_rate",
     "varuna_debug_set_gemm_kernels",
 )
 
@@ -101,6 +101,8 @@ def load():
         "varuna_op_layernorm_bwd": (i32, [i32, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "varuna_op_colsum": (i32, [i32, i64, i64, vp, vp, vp, vp]),
         "varuna_op_colreduce_scratch_bytes": (sz, [i64, i64]),
+        "varuna_op_colsum_static": (i32, [i32, i64, i64, vp, vp, vp]),
+        "varuna_op_colsum_static_max_bytes": (sz, []),
         "varuna_debug_set_gemm_kernels": (i32, [i32] * 6),
         "varuna_probe_mfma_rate": (i32, [vp, i64, i32, i32, i32, vp, C.POINTER(C.c_double), vp]),
         "varuna_op_attention_fwd": (i32, [i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]),
@@ -291,6 +293,15 @@ def op_layernorm_bwd(dy, x, stats, gamma, res, dx, dgamma, dbeta, partial, strea
 def op_colsum(a, out, partial, stream=None):
     rows, n = a.shape
     _check(load().varuna_op_colsum(dtype_code(a), rows, n, _ptr(a), _ptr(out), _ptr(partial), _stream_ptr(stream)))
+
+
+def op_colsum_static(a, out, stream=None):
+    rows, n = a.shape
+    _check(load().varuna_op_colsum_static(dtype_code(a), rows, n, _ptr(a), _ptr(out), _stream_ptr(stream)))
+
+
+def colsum_static_max_bytes() -> int:
+    return load().varuna_op_colsum_static_max_bytes()
 
 
 def debug_set_gemm_kernels(fwd256=0, dgrad256=0, wgrad256=0, fwd128=0, dgrad128=0, wgrad128=0):

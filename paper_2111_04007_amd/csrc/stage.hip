@@ -20,6 +20,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -917,6 +918,52 @@ varuna_status_t varuna_op_colsum(int32_t dtype, int64_t rows, int64_t n, const v
   else if (dtype == VARUNA_BF16) e = launch_colsum<bf16>(static_cast<const bf16*>(a), out_f32, partial_f32, rows, n, s);
   else return fail(VARUNA_EINVAL, "unknown dtype %d", dtype);
   return hip_result(e, "varuna_op_colsum");
+}
+
+// ---- column sums with no allocation anywhere ------------------------------------------
+// The stage-1 partial sums of varuna_op_colsum_static live in this file-scope device array
+// (every GPU the library runs on holds its own copy until the process ends).  In host code
+// the array's name is only a stand-in; the device address comes from hipGetSymbolAddress,
+// once per device, and is what the kernels receive.
+constexpr size_t kStaticScratchFloats = (size_t)1 << 20;   // 4 MiB
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+constexpr int kMaxDevices = 64;
+static float* g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mu;
+
+static varuna_status_t static_scratch(float** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(VARUNA_EUNSUPPORTED, "device index %d out of range", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(VARUNA_EHIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return VARUNA_OK;
+}
+
+size_t varuna_op_colsum_static_max_bytes(void) { return kStaticScratchFloats * sizeof(float); }
+
+varuna_status_t varuna_op_colsum_static(int32_t dtype, int64_t rows, int64_t n, const void* a, float* out_f32, void* hip_stream) {
+  if (rows < 1 || n < 1 || !a || !out_f32) return fail(VARUNA_EINVAL, "bad colsum arguments");
+  if (dtype != VARUNA_F32 && dtype != VARUNA_BF16) return fail(VARUNA_EINVAL, "unknown dtype %d", dtype);
+  const size_t need = varuna_op_colreduce_scratch_bytes(rows, n);
+  if (rows > (1ll << 40) || n > (1ll << 40) || need > kStaticScratchFloats * sizeof(float))
+    return fail(VARUNA_EUNSUPPORTED, "colsum of [%lld, %lld] needs %zu bytes of partial sums; the built-in scratch holds %zu",
+                (long long)rows, (long long)n, need, kStaticScratchFloats * sizeof(float));
+  float* partial = nullptr;
+  varuna_status_t rc = static_scratch(&partial);
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  // stage 1 overwrites every partial that stage 2 reads, so nothing has to be cleared
+  if (dtype == VARUNA_F32) e = launch_colsum<float>(static_cast<const float*>(a), out_f32, partial, rows, n, s);
+  else e = launch_colsum<bf16>(static_cast<const bf16*>(a), out_f32, partial, rows, n, s);
+  return hip_result(e, "varuna_op_colsum_static");
 }
 
 varuna_status_t varuna_debug_set_gemm_kernels(int32_t fwd256, int32_t dgrad256, int32_t wgrad256, int32_t fwd128,

@@ -46,6 +46,10 @@ def parse():
     ap.add_argument("--ceiling", action="store_true",
                     help="instead of the step benchmark, measure what the matrix cores sustain when fed from registers "
                          "only (v_mfma_f32_32x32x16_bf16 on normally distributed and on all-zero operands)")
+    ap.add_argument("--energy", action="store_true",
+                    help="instead of the step benchmark, measure energy per FLOP (the GPU's accumulated-energy counter "
+                         "read through rocm-smi over windows of several seconds) of the register-only MFMA loop, of this "
+                         "library's forward GEMM on two C5 shapes, and of the vendor library's GEMM as a reference point")
     ap.add_argument("--no-ungrouped", action="store_true",
                     help="skip the second measurement of the same step with wgrad_group=1 (the configuration as "
                          "specified: weight gradients accumulated after every micro-batch)")
@@ -168,7 +172,7 @@ def bench_ceiling(args):
     stream = torch.cuda.current_stream()
     iters = 200000      # about 0.1 s per launch
     rows = []
-    cases = [(name, wps, 0) for name in data for wps in (1, 2)] + [("normal(0,1)", 2, pat) for pat in (1, 2, 3)]
+    cases = [(name, wps, 0) for name in data for wps in (1, 2)] + [("normal(0,1)", 2, pat) for pat in (1, 2, 3, 4, 5)]
     for name, wps, pat in cases:
         t = data[name]
         if True:
@@ -235,6 +239,9 @@ def main():
         return
     if args.ceiling:
         print(json.dumps(bench_ceiling(args)))
+        return
+    if args.energy:
+        print(json.dumps(bench_energy(args)))
         return
     if args.micro_batches:
         cfg = cfg.replace(n_micro_batches=args.micro_batches)
@@ -437,6 +444,72 @@ def main():
     }
     st.close()
     print(json.dumps(out))
+
+
+def _energy_joules():
+    """The GPU's accumulated-energy counter in joules, or None (rocm-smi missing or no such counter)."""
+    import subprocess
+    try:
+        out = subprocess.run(["rocm-smi", "--showenergycounter", "--json"], capture_output=True, text=True, timeout=20).stdout
+        card = next(iter(json.loads(out).values()))
+        for k, v in card.items():
+            if "uJ" in k:
+                return float(v) * 1e-6
+    except Exception:
+        pass
+    return None
+
+
+def bench_energy(args):
+    """Energy per FLOP under the board power limit.  Every kernel here runs the chip into its power
+    cap on normally distributed operands, so its rate is set by the energy it spends per product;
+    the counter is read before and after a window of `--steps` seconds of back-to-back launches."""
+    import torch
+    from paper_2111_04007_amd import binding as B, flops
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    window = float(max(4, args.steps))
+    gen = torch.Generator(device=dev).manual_seed(20211104)
+    dt = torch.bfloat16
+    rows = []
+
+    def run(label, fn, fl):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, t0, n = _energy_joules(), time.perf_counter(), 0
+        while time.perf_counter() - t0 < window:
+            for _ in range(20):
+                fn()
+            torch.cuda.synchronize()
+            n += 20
+        t1, e1 = time.perf_counter(), _energy_joules()
+        row = {"kernel": label, "tflops": fl * n / (t1 - t0) / 1e12, "seconds": t1 - t0}
+        if e0 is not None and e1 is not None:
+            row.update({"watts": (e1 - e0) / (t1 - t0), "pj_per_flop": (e1 - e0) / (fl * n) * 1e12})
+        rows.append(row)
+
+    src = torch.empty(1 << 23, device=dev, dtype=torch.float32).normal_(generator=gen).to(dt)
+    sink = torch.empty(torch.cuda.get_device_properties(dev).multi_processor_count * 2 * 256, device=dev)
+    fl_probe = B.probe_mfma_rate(src, 2, 20000, sink, 0)
+    run("register-only MFMA loop, normal(0,1)", lambda: B.probe_mfma_rate(src, 2, 20000, sink, 0), fl_probe)
+    for name, (M, N, K) in (("QKV", (2048, 24576, 8192)), ("MLP2", (2048, 8192, 32768))):
+        a = torch.empty(M, K, device=dev, dtype=torch.float32).normal_(generator=gen).to(dt)
+        b = (torch.empty(N, K, device=dev, dtype=torch.float32).normal_(generator=gen) * 0.01).to(dt)
+        bias = torch.zeros(N, device=dev, dtype=dt)
+        out = torch.empty(M, N, device=dev, dtype=dt)
+        fl = 2.0 * M * N * K
+        run(f"forward GEMM {name} {M}x{N}x{K}, this library (library's choice of kernel)",
+            lambda: B.op_gemm(B.OP_FWD, 0, a, b, out, bias=bias, variant=0, M=M, N=N, K=K), fl)
+        run(f"forward GEMM {name} {M}x{N}x{K}, 256x256 tile on 8 waves with two stages (variant 5)",
+            lambda: B.op_gemm(B.OP_FWD, 0, a, b, out, bias=bias, variant=5, M=M, N=N, K=K), fl)
+        run(f"same product through torch.matmul (vendor library; reference point only)",
+            lambda: torch.matmul(a, b.t(), out=out), fl)
+    return {"metric": "energy per FLOP at the board power limit", "value": rows[1].get("pj_per_flop"), "unit": "pJ/FLOP",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": False, "dtype": "bf16",
+            "data": "synthetic", "vs_baseline": None,
+            "config": {"workload": "C5 forward GEMM shapes, back-to-back launches", "window_seconds": window,
+                       "nominal_peak_tflops": flops.MI355X_BF16_DENSE_PEAK / 1e12}, "rows": rows}
 
 
 def bench_tail(cfg, args):

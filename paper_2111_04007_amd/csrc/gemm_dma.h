@@ -282,7 +282,9 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
       if constexpr (J < LA1) la.template issue_one<J>(smem + STAGE_ELEMS, kt0 + 1, iw, nk > 1);
       else lb.template issue_one<J - LA1>(smem + STAGE_ELEMS + BM * DG_BK, kt0 + 1, iw, nk > 1);
     });
-    __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(N31));
+    // (a load whose descriptor covers zero bytes makes no memory request and may retire ahead of
+    // older loads still in flight: counting outstanding loads is only valid among live ones)
+    if (nk > 1) __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(N31)); else __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(0));
   } else if constexpr (LS == 2) {
     // A(0), B(0) whole, then B(1) whole and the first half of A(1): what the steady state has sent
     // for tile 0's barrier-to-barrier period by the time its k-step 0 starts.
@@ -291,7 +293,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
     lb.issue(b_stage(0), kt0, iw);
     dg_static_for<LB2>([&](auto j_tag) { lb.template issue_one<decltype(j_tag)::value>(b_stage(1), kt0 + 1, iw, nk > 1); });
     dg_static_for<LA2 / 2>([&](auto j_tag) { la.template issue_one<decltype(j_tag)::value>(a_stage(1), kt0 + 1, iw, nk > 1); });
-    __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LB2 + LA2 / 2));
+    if (nk > 1) __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LB2 + LA2 / 2)); else __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(0));
   } else if (issuer) {
     la.issue(smem, kt0, iw);
     lb.issue(smem + BM * DG_BK, kt0, iw);
@@ -454,9 +456,12 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
       kstep(S0{}, ca, cb, 1, DgLoads<LA / 2, LA>{}, na, kt0 + kt + 1, live1, nnb, 0, false);
       kstep(S1{}, ca, cb, 2, DgLoads<LA, LA + LB / 2>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
       kstep(S0{}, ca, cb, 3, DgLoads<LA + LB / 2, LT>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
-      // tile kt+1 has landed (A's second half went out three k-steps ago, B's a period ago); the
-      // LB loads of B(kt+2) sent since then may still be in flight
-      __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LB) & DG_WAIT_LGKM0);
+      // tile kt+1 must have landed (A's second half went out three k-steps ago, B's a period ago); the
+      // LB loads of B(kt+2) sent since then may still be in flight.  That count holds only while
+      // those loads are live: past the end of the reduction they make no memory request and may
+      // retire ahead of older loads, so the last two k-tiles wait for everything.
+      if (live2) __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LB) & DG_WAIT_LGKM0);
+      else __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
       __builtin_amdgcn_s_barrier();
       kstep(S1{}, na, nb, 0, DgLoads<0, LA / 2>{}, ca, kt0 + kt + 2, live2, nnb, 0, false);
       bs = bs1;
@@ -596,11 +601,13 @@ inline int dg_choose_variant(int64_t M, int64_t N, int64_t K, int64_t lda, int64
 }
 
 // Kernel configuration for a product once the tile size is chosen (tile_variant 5: 256x256, 7:
-// 128x128), as measured on normally distributed operands at the stage shapes: the 256x256 forward
-// product runs best on 4 waves (128x128 per wave: a third fewer LDS reads per product) with the
-// loads sent in every k-step; the products with a transposing operand keep 8 waves (two per SIMD
-// hide each other's waits on the two-instruction transposed reads) with the same load schedule.
-struct DgFlavours { int fwd256 = 13, bwd256 = 12, fwd128 = 14, dgrad128 = 14, wgrad128 = 7, wgrad256 = 12; };
+// 128x128), picked by timing whole stage steps with each combination in one process (the chip
+// runs the step at its board power limit, so what counts is energy per product, not the rate of
+// a kernel alone): the 256x256 forward product runs on 4 waves (128x128 per wave: a third fewer
+// LDS reads per product) with a third B stage and loads in every k-step; dgrad keeps 8 waves
+// (two per SIMD hide each other's waits on the two-instruction transposed reads) with the same
+// load schedule; wgrad, both of whose operands are read transposed, keeps the two-stage kernel.
+struct DgFlavours { int fwd256 = 13, bwd256 = 12, fwd128 = 14, dgrad128 = 14, wgrad128 = 7, wgrad256 = 5; };
 inline DgFlavours& dg_flavours() { static DgFlavours f; return f; }   // tuning hook: varuna_debug_set_gemm_kernels
 inline int dg_flavour(int tile_variant, int op) {
   const DgFlavours& f = dg_flavours();

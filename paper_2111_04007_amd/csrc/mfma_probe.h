@@ -15,7 +15,10 @@ namespace varuna {
 //   0: both operands change from one product to the next;
 //   1: the first operand is held for 8 consecutive products, the second changes every time;
 //   2: the first is held for 8, the second for 2 (the order a 4x2 register tile walked row by row gives);
-//   3: both operands are the same fragments for every product.
+//   3: both operands are the same fragments for every product;
+//   4: as 0, but 4 consecutive products add to the same accumulator tile (a dependent chain, as
+//      when the products of 4 k-steps of one output block are issued back to back);
+//   5: as 4 with chains of 2.
 template <int PATTERN>
 __global__ __launch_bounds__(256) void mfma_rate_kernel(const bf16x8* __restrict__ src, uint32_t n_vec,
                                                         float* __restrict__ sink, int iters) {
@@ -36,9 +39,15 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(const bf16x8* __restrict
     for (int u = 0; u < 4; ++u)
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const int ia = PATTERN == 0 ? (i & 3) : (PATTERN == 3 ? 0 : u);
-        const int ib = PATTERN == 0 ? ((i + u) & 3) : (PATTERN == 1 ? (i & 3) : (PATTERN == 2 ? ((i >> 1) & 3) : 0));
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ia], b[ib], acc[i], 0, 0, 0);
+        if (PATTERN >= 4) {   // product number n = 8u + i of 32: accumulator changes every CH products
+          constexpr int CH = PATTERN == 4 ? 4 : 2;
+          const int n = 8 * u + i, t = (n / CH) & 7;
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[n & 3], b[(n + (n >> 2)) & 3], acc[t], 0, 0, 0);
+        } else {
+          const int ia = PATTERN == 0 ? (i & 3) : (PATTERN == 3 ? 0 : u);
+          const int ib = PATTERN == 0 ? ((i + u) & 3) : (PATTERN == 1 ? (i & 3) : (PATTERN == 2 ? ((i >> 1) & 3) : 0));
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ia], b[ib], acc[i], 0, 0, 0);
+        }
       }
   }
   float s = 0.f;

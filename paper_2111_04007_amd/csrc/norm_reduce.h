@@ -361,11 +361,10 @@ inline void launch_colreduce_partial(const T* a, const T* x, const float* stats,
 
 inline int colreduce_chunks(int64_t rows) { return (int)((rows + CR_CHUNK - 1) / CR_CHUNK); }
 
-// dx plus the gamma/beta gradient accumulation (three launches).
+// dx = res + LN'(dy) alone (one launch).
 template <typename T>
-inline hipError_t launch_layernorm_bwd(const T* dy, const T* x, const float* stats, const T* gamma,
-                                       const T* res, T* dx, float* dgamma, float* dbeta,
-                                       float* partial, int64_t rows, int h, hipStream_t st) {
+inline hipError_t launch_layernorm_bwd_dx(const T* dy, const T* x, const float* stats, const T* gamma,
+                                          const T* res, T* dx, int64_t rows, int h, hipStream_t st) {
   dim3 grid((unsigned)((rows + LN_ROWS_PER_BLOCK - 1) / LN_ROWS_PER_BLOCK)), block(LN_ROWS_PER_BLOCK * kWave);
   constexpr int V = ln_vec<T>();
   if (h % V == 0 && ln_aligned16({dy, x, gamma, res, dx})) {
@@ -376,10 +375,28 @@ inline hipError_t launch_layernorm_bwd(const T* dy, const T* x, const float* sta
     else hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, V>), grid, block, 0, st, dy, x, stats, gamma, res, dx, rows, h);
   } else
     hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, 1>), grid, block, 0, st, dy, x, stats, gamma, res, dx, rows, h);
+  return hipGetLastError();
+}
+
+// dgamma += sum_t dy * xhat, dbeta += sum_t dy (two launches; they read dy, x and the statistics only,
+// so they need not run on the stream that carries dx).
+template <typename T>
+inline hipError_t launch_layernorm_bwd_params(const T* dy, const T* x, const float* stats, float* dgamma, float* dbeta,
+                                              float* partial, int64_t rows, int h, hipStream_t st) {
   const int nch = colreduce_chunks(rows);
   launch_colreduce_partial<T, 1>(dy, x, stats, partial, rows, (int64_t)h, st);
   hipLaunchKernelGGL(colreduce_final_kernel, dim3((unsigned)((h + 255) / 256)), dim3(256), 0, st, partial, nch, (int64_t)h, dgamma, dbeta);
   return hipGetLastError();
+}
+
+// dx plus the gamma/beta gradient accumulation (three launches).
+template <typename T>
+inline hipError_t launch_layernorm_bwd(const T* dy, const T* x, const float* stats, const T* gamma,
+                                       const T* res, T* dx, float* dgamma, float* dbeta,
+                                       float* partial, int64_t rows, int h, hipStream_t st) {
+  hipError_t e = launch_layernorm_bwd_dx<T>(dy, x, stats, gamma, res, dx, rows, h, st);
+  if (e != hipSuccess) return e;
+  return launch_layernorm_bwd_params<T>(dy, x, stats, dgamma, dbeta, partial, rows, h, st);
 }
 
 template <typename T>

@@ -130,7 +130,7 @@ struct Workspace {
   LayerArea fwd;                 // scratch of the forward pass (nothing of it is kept)
   size_t saved_begin, saved_end;
   size_t ping[2];                // forward layer outputs (discarded)
-  size_t dxn, dctx, delta, partial;
+  size_t dxn, dxn_b, dctx, delta, partial;   // dxn: gradient of LN2's output, dxn_b: of LN1's
   size_t partial_side;           // reduction partials of the bias-gradient sums that run on the side stream
   size_t stat_partial;           // partial sums of the gradient statistics (doubles)
   size_t splitk, splitk_size;    // partial weight gradients of split-K GEMMs (fp32); size 0 if no GEMM splits
@@ -174,7 +174,7 @@ Workspace carve(const Dims& D) {
   }
   w.fwd = area(1, false);
   w.ping[0] = take(E); w.ping[1] = take(E);
-  w.dxn = take(E); w.dctx = take(E);
+  w.dxn = take(E); w.dxn_b = take(E); w.dctx = take(E);
   w.delta = take(lse);
   int64_t widest = 3 * (int64_t)D.h;
   if (D.f > widest) widest = D.f;
@@ -381,16 +381,30 @@ struct StageOps {
     return gemm(VARUNA_K_GEMM_FWD, GEMM_FWD, EPI_BIAS_RES, T_, D.h, D.f, g, param(l, VARUNA_P_W2), param(l, VARUNA_P_B2), x1, y, nullptr, nullptr, drop_args(DROP_SITE_MLP, l, mb));
   }
 
-  hipError_t colsum(const T* a, float* out, int64_t n) {
+  // Runs `launch(stream, partial scratch)` beside the GEMM chain when the caller has handed over a
+  // side stream: everything the launch reads is complete at this point of the caller's stream,
+  // and nothing on that stream depends on its result before the next join_side().
+  template <typename F>
+  hipError_t on_side(int cls, double bytes, F&& launch) {
     if (S->prof_on || S->side == nullptr) {  // per-kernel timing wants everything on one stream
-      Bracket br(S, st, VARUNA_K_COLREDUCE, 0, (double)D.T * n * sizeof(T));
-      return launch_colsum<T>(a, out, wsp<float>(S->ws.partial), D.T, n, st);
+      Bracket br(S, st, cls, 0, bytes);
+      return launch(st, wsp<float>(S->ws.partial));
     }
     hipError_t e;
-    if ((e = hipEventRecord(S->ev_fork, st))) return e;           // `a` is complete at this point of the caller's stream
+    if ((e = hipEventRecord(S->ev_fork, st))) return e;
     if ((e = hipStreamWaitEvent(S->side, S->ev_fork, 0))) return e;
     S->side_used = true;
-    return launch_colsum<T>(a, out, wsp<float>(S->ws.partial_side), D.T, n, S->side);
+    return launch(S->side, wsp<float>(S->ws.partial_side));
+  }
+  hipError_t colsum(const T* a, float* out, int64_t n) {
+    return on_side(VARUNA_K_COLREDUCE, (double)D.T * n * sizeof(T),
+                   [&](hipStream_t s, float* partial) { return launch_colsum<T>(a, out, partial, D.T, n, s); });
+  }
+  // gamma / beta gradients of one LayerNorm (reads dy, x, statistics)
+  hipError_t ln_params(const T* dyn, const T* x, const float* stats, float* dgamma, float* dbeta) {
+    return on_side(VARUNA_K_COLREDUCE, 2.0 * D.E * sizeof(T), [&](hipStream_t s, float* partial) {
+      return launch_layernorm_bwd_params<T>(dyn, x, stats, dgamma, dbeta, partial, D.T, D.h, s);
+    });
   }
 
   // The caller's stream waits for everything forked since the last join.
@@ -417,8 +431,8 @@ struct StageOps {
     const T* dy = wsp<T>(A.dy) + (size_t)rs * D.E;
     T* du = wsp<T>(A.du) + (size_t)rs * D.F; T* dx1 = wsp<T>(A.dx1) + (size_t)rs * D.E;
     T* dqkv = wsp<T>(A.dqkv) + (size_t)rs * 3 * D.E;
-    T* dxn = wsp<T>(W.dxn); T* dctx = wsp<T>(W.dctx);
-    float* delta = wsp<float>(W.delta); float* partial = wsp<float>(W.partial);
+    T* dxn = wsp<T>(W.dxn); T* dxn_b = wsp<T>(W.dxn_b); T* dctx = wsp<T>(W.dctx);
+    float* delta = wsp<float>(W.delta);
 
     // With dropout the gradient entering a residual branch is the masked one (dyd, dx1d); the
     // residual path itself keeps dy / dx1.
@@ -438,9 +452,10 @@ struct StageOps {
     if ((e = colsum(du, grad(l, VARUNA_P_B1), D.f))) return e;
     // LN2: dx1 = dy + LN'(dxn2)
     {
-      Bracket br(S, st, VARUNA_K_LN_BWD, 0, 6.0 * D.E * sizeof(T));
-      if ((e = launch_layernorm_bwd<T>(dxn, x1, stats2, param(l, VARUNA_P_LN2_G), dy, dx1, grad(l, VARUNA_P_LN2_G), grad(l, VARUNA_P_LN2_B), partial, T_, D.h, st))) return e;
+      Bracket br(S, st, VARUNA_K_LN_BWD, 0, 4.0 * D.E * sizeof(T));
+      if ((e = launch_layernorm_bwd_dx<T>(dxn, x1, stats2, param(l, VARUNA_P_LN2_G), dy, dx1, T_, D.h, st))) return e;
     }
+    if ((e = ln_params(dxn, x1, stats2, grad(l, VARUNA_P_LN2_G), grad(l, VARUNA_P_LN2_B)))) return e;
     const T* dx1d = dx1;
     if (dr) {
       T* o = wsp<T>(A.dx1d) + (size_t)rs * D.E;
@@ -457,14 +472,16 @@ struct StageOps {
       if ((e = AttnDispatch<T>::bwd(0, qkv, ctx, lse, dctx, dqkv, delta, D.b, D.s, D.a, D.d, D.causal, drop_args(DROP_SITE_ATTN, l, mb), st))) return e;
     }
     // QKV: dxn1 = dqkv Wqkv; dbqkv += colsum(dqkv)
-    if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_PLAIN, T_, D.h, 3 * D.h, dqkv, param(l, VARUNA_P_WQKV), nullptr, nullptr, dxn, nullptr, nullptr))) return e;
+    if ((e = gemm(VARUNA_K_GEMM_DGRAD, GEMM_DGRAD, EPI_PLAIN, T_, D.h, 3 * D.h, dqkv, param(l, VARUNA_P_WQKV), nullptr, nullptr, dxn_b, nullptr, nullptr))) return e;
     if ((e = colsum(dqkv, grad(l, VARUNA_P_BQKV), 3 * D.h))) return e;
     // LN1: dx = dx1 + LN'(dxn1)
     {
-      Bracket br(S, st, VARUNA_K_LN_BWD, 0, 6.0 * D.E * sizeof(T));
-      if ((e = launch_layernorm_bwd<T>(dxn, x, stats1, param(l, VARUNA_P_LN1_G), dx1, dx, grad(l, VARUNA_P_LN1_G), grad(l, VARUNA_P_LN1_B), partial, T_, D.h, st))) return e;
+      Bracket br(S, st, VARUNA_K_LN_BWD, 0, 4.0 * D.E * sizeof(T));
+      if ((e = launch_layernorm_bwd_dx<T>(dxn_b, x, stats1, param(l, VARUNA_P_LN1_G), dx1, dx, T_, D.h, st))) return e;
     }
-    return hipSuccess;
+    if ((e = ln_params(dxn_b, x, stats1, grad(l, VARUNA_P_LN1_G), grad(l, VARUNA_P_LN1_B)))) return e;
+    // the next layer down rewrites dxn / dxn_b and this layer's rings: the side stream's reads come first
+    return join_side();
   }
 
   // One weight gradient dW[M,N] += A^T B over K tokens.  bf16 shapes with too few output
@@ -984,7 +1001,7 @@ varuna_status_t varuna_debug_set_gemm_kernels(int32_t fwd256, int32_t dgrad256, 
 
 varuna_status_t varuna_probe_mfma_rate(const void* operands, int64_t n_elems, int32_t waves_per_simd, int32_t pattern,
                                        int32_t iters, float* sink, double* flops, void* hip_stream) {
-  if (pattern < 0 || pattern > 3) return fail(VARUNA_EINVAL, "pattern must be in [0, 3]");
+  if (pattern < 0 || pattern > 5) return fail(VARUNA_EINVAL, "pattern must be in [0, 5]");
   if (!operands || !sink) return fail(VARUNA_EINVAL, "NULL pointer");
   if (n_elems < 8 || n_elems > (1ll << 31) || n_elems % 8 != 0) return fail(VARUNA_EINVAL, "n_elems must be a multiple of 8 in [8, 2^31]");
   if (reinterpret_cast<uintptr_t>(operands) % 16 != 0) return fail(VARUNA_EINVAL, "operands must be 16-byte aligned");
@@ -1002,7 +1019,9 @@ varuna_status_t varuna_probe_mfma_rate(const void* operands, int64_t n_elems, in
     case 0: hipLaunchKernelGGL(mfma_rate_kernel<0>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
     case 1: hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
     case 2: hipLaunchKernelGGL(mfma_rate_kernel<2>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
-    default: hipLaunchKernelGGL(mfma_rate_kernel<3>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
+    case 3: hipLaunchKernelGGL(mfma_rate_kernel<3>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
+    case 4: hipLaunchKernelGGL(mfma_rate_kernel<4>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
+    default: hipLaunchKernelGGL(mfma_rate_kernel<5>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
   }
   if (flops) *flops = (double)nwg * 4.0 * (double)iters * 8.0 * (2.0 * 32 * 32 * 16);
   return hip_result(hipGetLastError(), "varuna_probe_mfma_rate");

@@ -202,3 +202,69 @@ def test_attention_mfma_rejects_unsupported_shape():
     with pytest.raises(B.VarunaError) as ei:
         B.op_attention_fwd(qkv, ctx, None, 1, 100, 1, 64, 1, variant=1)
     assert ei.value.code == B.EUNSUPPORTED
+
+
+@pytest.mark.parametrize("variant", [12, 13, 14, 9])
+def test_gemm_bit_stable_under_memory_contention(variant):
+    """The kernels that keep loads in flight across a barrier must not let a k-tile be read
+    before it has landed when memory latency rises (a wait that counted loads past the end of
+    the reduction as outstanding once let the last k-tiles through early; the whole-step
+    determinism tests are what caught it).  The same product is repeated while a second stream
+    keeps HBM busy with copies; every repetition must be bit-identical to the first, for
+    reductions of 1, 2, 3 and many k-tiles and all three operand layouts."""
+    side = torch.cuda.Stream()
+    big = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    big2 = torch.empty_like(big)
+    M, N = 1024, 1536
+    for K in (64, 128, 192, 1024):
+        x = rnd((M, K), "bf16", 40 + K)
+        w = rnd((N, K), "bf16", 41 + K, 0.05)
+        wd = rnd((K, N), "bf16", 42 + K, 0.05)
+        dy = rnd((K, M), "bf16", 43 + K)
+        xx = rnd((K, N), "bf16", 44 + K)
+        bias = rnd((N,), "bf16", 45 + K, 0.5)
+        torch.cuda.synchronize()
+
+        def products():
+            o1 = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+            o2 = torch.empty_like(o1)
+            o3 = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+            B.op_gemm(B.OP_FWD, 0, x, w, o1, bias=bias, variant=variant, M=M, N=N, K=K)
+            B.op_gemm(B.OP_DGRAD, 0, x, wd, o2, variant=variant, M=M, N=N, K=K)
+            B.op_gemm(B.OP_WGRAD, 0, dy, xx, o3, variant=variant, M=M, N=N, K=K)
+            return o1, o2, o3
+
+        ref = products()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            for _ in range(12):
+                big2.copy_(big, non_blocking=True)
+        outs = [products() for _ in range(8)]
+        torch.cuda.synchronize()
+        for o in outs:
+            for got, want in zip(o, ref):
+                assert torch.equal(got, want), (variant, K)
+
+
+@pytest.mark.parametrize("variant", [5, 6, 7, 8, 9, 10, 11, 12, 13, 14])
+def test_gemm_bf16_variants_to_rounding_accuracy(variant):
+    """The whole-stage tolerance (2e-2) would hide a k-tile read before it landed or dropped from
+    a long reduction.  Here every kernel configuration is held to what its arithmetic allows: the
+    fp32 weight-gradient accumulator to 1e-5, bf16 outputs to the rounding of the output itself
+    (rel-L2 about 2^-9 / sqrt(3) = 1.1e-3), for reductions of 1 to 16 k-tiles."""
+    M, N = 512, 768
+    for K in (64, 128, 192, 256, 1024):
+        x = rnd((M, K), "bf16", 60 + K)
+        w = rnd((N, K), "bf16", 61 + K, 0.05)
+        wd = rnd((K, N), "bf16", 62 + K, 0.05)
+        dy = rnd((K, M), "bf16", 63 + K)
+        xx = rnd((K, N), "bf16", 64 + K)
+        bias = rnd((N,), "bf16", 65 + K, 0.5)
+        out = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        B.op_gemm(B.OP_FWD, 0, x, w, out, bias=bias, variant=variant, M=M, N=N, K=K)
+        assert O.rel_l2(to_f64(out), O.linear_forward(to_f64(x), to_f64(w), to_f64(bias))) <= 2.5e-3, K
+        B.op_gemm(B.OP_DGRAD, 0, x, wd, out, variant=variant, M=M, N=N, K=K)
+        assert O.rel_l2(to_f64(out), to_f64(x) @ to_f64(wd)) <= 2.5e-3, K
+        acc = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+        B.op_gemm(B.OP_WGRAD, 0, dy, xx, acc, variant=variant, M=M, N=N, K=K)
+        assert O.rel_l2(to_f64(acc), to_f64(dy).T @ to_f64(xx)) <= 1e-5, K

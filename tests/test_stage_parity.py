@@ -242,7 +242,7 @@ def test_accumulation_reset_and_determinism():
         s.close()
 
 
-@pytest.mark.parametrize("name", ["C2", "C4"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C4"])
 def test_bf16_run_to_run_determinism_at_full_shape(name):
     """The bf16 path (MFMA GEMMs with split-K weight gradients, MFMA attention, bias-gradient
     sums on the side stream, grouped weight-gradient GEMMs) gives bit-identical outputs, input

@@ -277,7 +277,8 @@ varuna_status_t varuna_stage_profile_collect(varuna_stage_t* st, double* ms, int
  * of its 4 + 4 fragments consecutive products read: 0 both operands change every product,
  * 1 the first is held for 8 products, 2 the first for 8 and the second for 2 (a 4x2 register
  * tile walked row by row), 3 both always the same, 4 / 5 as 0 with 4 / 2 consecutive products
- * adding to the same accumulator tile.  The caller times the
+ * adding to the same accumulator tile, 6 / 7 as 0 / 2 with two v_mfma_f32_16x16x32_bf16 in
+ * place of every 32x32x16 product (the same operation count).  The caller times the
  * launch with events on hip_stream; *flops (host, may be NULL) receives the floating-point
  * operations of the launch.  sink: device, compute_units * waves_per_simd * 256 floats,
  * receives accumulator sums (so the products cannot be elided).  The rate depends on the

@@ -12,7 +12,7 @@
 //   k-major operand : [row][64 k]  (128 B per row, 8 chunks of 16 B),
 //                     physical chunk = c ^ ((row ^ (row >> 3)) & 7); fragments by ds_read_b128.
 //   m/n-major operand: [k][ROWS]   (ROWS*2 B per k-row), physical chunk within each
-//                     group of 8 = c ^ ((k & 3) << 1); fragments by the transposing
+//                     group of 16 = c ^ dg_tr_swizzle(k); fragments by the transposing
 //                     LDS read ds_read_b64_tr_b16 (16 lanes x 4 k-rows -> each lane
 //                     gets 4 consecutive k of its own row), two per 8-k operand.
 // Both give a lane the 8 consecutive k-values (lane/32)*8.. of tile row lane%32,
@@ -39,12 +39,20 @@ typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
 // Direct global->LDS staging of one operand tile (ROWS x 64).
 //   k-major  : LDS [row][64 k], 8 chunks of 16 B per row, physical chunk = c ^ ((row ^ (row >> 3)) & 7)
-//   m/n-major: LDS [k][ROWS],   physical chunk (within each aligned group of 8) = c ^ ((k & 3) << 1)
+//   m/n-major: LDS [k][ROWS],   physical chunk (within each aligned group of 16) = c ^ dg_tr_swizzle(k)
+// A transposing read takes, per 16 lanes, 32 B from each of 4 consecutive k-rows, and per 32 lanes 64 B
+// from each; k-rows are a multiple of 256 B apart, so unswizzled all four start in the same bank.  The
+// XOR values 0, 6, 12, 10 differ both in bits 1-2 and in bits 2-3 of the chunk number: the four rows'
+// 32-byte pieces fall into different quarters of 128 B and their 64-byte pieces into different quarters
+// of 256 B, which is free of bank conflicts whether the LDS serves 16 or 32 lanes of such a read at once.
+__device__ __forceinline__ constexpr int dg_tr_swizzle(int k) { return ((k & 1) * 6) ^ (((k >> 1) & 1) * 12); }
+
 template <int ROWS, int NW, bool KMAJOR>
 struct DgLoader {
   static constexpr int NINS = ROWS * DG_BK * 2 / 1024;  // wave-level 1 KB loads per tile
   static constexpr int LPT = NINS / NW;                  // per wave
   static_assert(NINS % NW == 0 && LPT >= 1, "tile rows / waves mismatch");
+  static_assert(KMAJOR || ROWS % 128 == 0, "the m/n-major swizzle permutes groups of 16 chunks");
   const bf16* base;             // the whole operand is one buffer; loads beyond its extent return zero
   uint32_t extent;
   uint32_t voff[LPT];           // per-lane byte offset of each of this wave's loads (k-tile 0)
@@ -63,7 +71,7 @@ struct DgLoader {
       } else {
         constexpr int CPR = ROWS / 8;  // chunks per k-row
         const int slot = q * 64 + lane, krow = slot / CPR, p = slot % CPR;
-        const int c = p ^ ((krow & 3) << 1);
+        const int c = p ^ dg_tr_swizzle(krow);
         voff[i] = (uint32_t)(((int64_t)krow * ld + row0 + c * 8) * 2);
       }
     }
@@ -140,7 +148,7 @@ struct DgFrag {
       const int blk = lane >> 4, j = lane & 15;
       const int m = row_base + (blk & 1) * 16 + 4 * (j & 3);
       const int kq = j >> 2;  // k-row within its group of 4 == (krow & 3)
-      const int c = m >> 3, phys = c ^ (kq << 1);
+      const int c = m >> 3, phys = c ^ dg_tr_swizzle(kq);
       const bf16* p0 = lds_tile + (ks * 16 + (blk >> 1) * 8 + kq) * ROWS + phys * 8 + (m & 7);
       const uint32_t a0 = (uint32_t)(uintptr_t)(lds_ptr_t)const_cast<bf16*>(p0);
       const uint32_t a1 = a0 + 4 * ROWS * 2;
@@ -195,6 +203,40 @@ struct DgInterleaveMask {
     }
   }
 };
+
+// bf16 epilogue of one wave's (TM*32) x WN sub-tile whose first output is (row0, col0), through a
+// private LDS buffer of 32 rows x WN floats.  acc[i][j][r] is row m = lane%32 of the 32x32 block,
+// column n = 8*(r/4) + 4*(lane/32) + r%4.
+template <int MODE, int TM, int TN, int WN>
+__device__ __forceinline__ void dg_epilogue_bf16(floatx16 (&acc)[TM][TN], unsigned char* buf, const EpiArgs<bf16>& epi,
+                                                 int64_t row0, int64_t col0, int lane) {
+  constexpr int ROWB = WN * 4;              // bytes per staged fp32 row
+  constexpr int LPR = WN / 8;               // lanes per output row (8 columns each)
+  constexpr int RPI = 64 / LPR;             // rows per store instruction
+  const int frow = lane & 31, fchunk = lane >> 5;
+  const int rrow = lane / LPR, rcol = (lane % LPR) * 8;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int c = j * 8 + g * 2 + fchunk;
+        floatx4 v = {acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
+        *reinterpret_cast<floatx4*>(buf + frow * ROWB + (((c & ~15) | ((c ^ frow) & 15)) << 4)) = v;
+      }
+    __builtin_amdgcn_s_waitcnt(DG_WAIT_LGKM0);  // own writes landed (the buffer is private to the wave)
+#pragma unroll
+    for (int sub = 0; sub < 32 / RPI; ++sub) {
+      const int r = sub * RPI + rrow, c0 = rcol / 4;
+      const floatx4 lo = *reinterpret_cast<const floatx4*>(buf + r * ROWB + (((c0 & ~15) | ((c0 ^ r) & 15)) << 4));
+      const floatx4 hi = *reinterpret_cast<const floatx4*>(buf + r * ROWB + ((((c0 + 1) & ~15) | (((c0 + 1) ^ r) & 15)) << 4));
+      float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      gemm_epilogue8<MODE>(epi, row0 + i * 32 + r, col0 + rcol, v);
+    }
+    __builtin_amdgcn_s_waitcnt(DG_WAIT_LGKM0);  // reads done before the next pass overwrites
+  }
+}
 
 // LS (load schedule): 0 = the loads of a k-tile go out in one run right after the barrier that
 // frees their stage (from the upper half of the waves, or from both halves one k-step apart,
@@ -266,9 +308,15 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
   const int nk = K / DG_BK / (int)gridDim.y;
   const int kt0 = (int)blockIdx.y * nk;
   // LDS map.  LS 0, 1: two stages of [A tile | B tile].  LS 2: two stages of A, then three of B.
-  constexpr int A_STRIDE = (LS == 2) ? BM * DG_BK : STAGE_ELEMS;
-  constexpr int B_STRIDE = (LS == 2) ? BN * DG_BK : STAGE_ELEMS;
-  constexpr int B_BASE = (LS == 2) ? 2 * BM * DG_BK : BM * DG_BK;
+  constexpr int A_STRIDE = (LS >= 2) ? BM * DG_BK : STAGE_ELEMS;
+  constexpr int B_STRIDE = (LS >= 2) ? BN * DG_BK : STAGE_ELEMS;
+  constexpr int B_BASE = (LS >= 2) ? 2 * BM * DG_BK : BM * DG_BK;
+  // LS >= 2: which of a wave's loads (A's LA first, then B's LB) go out in the k-step after the barrier
+  // ([0, C3)), and in k-steps 0, 1, 2 of the next tile ([C3, C0), [C0, C1), [C1, LA+LB)).
+  constexpr int LA_ = DgLoader<BM, NI, A_KMAJOR>::LPT, LB_ = DgLoader<BN, NI, B_KMAJOR>::LPT;
+  // (Halves of A right after the barrier and in k-step 0, halves of B in k-steps 1 and 2; sending all of A
+  // right after the barrier, or three quarters of it, measured the same to half a percent.)
+  constexpr int C3 = LA_ / 2, C0 = LA_, C1 = LA_ + LB_ / 2;
   auto a_stage = [&](int i) { return smem + i * A_STRIDE; };
   auto b_stage = [&](int i) { return smem + B_BASE + i * B_STRIDE; };
   if constexpr (LS == 1) {
@@ -285,15 +333,15 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
     // (a load whose descriptor covers zero bytes makes no memory request and may retire ahead of
     // older loads still in flight: counting outstanding loads is only valid among live ones)
     if (nk > 1) __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(N31)); else __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(0));
-  } else if constexpr (LS == 2) {
-    // A(0), B(0) whole, then B(1) whole and the first half of A(1): what the steady state has sent
-    // for tile 0's barrier-to-barrier period by the time its k-step 0 starts.
-    constexpr int LA2 = DgLoader<BM, NI, A_KMAJOR>::LPT, LB2 = DgLoader<BN, NI, B_KMAJOR>::LPT;
+  } else if constexpr (LS >= 2) {
+    // A(0), B(0) whole, then B(1) whole and the loads of tile 1 that go out right after a barrier (all of
+    // them A's): what the steady state has sent for tile 0's period by the time its k-step 0 starts.
+    static_assert(C3 <= LA_ && C0 >= LA_, "only A's loads follow the barrier; A is complete after k-step 0");
     la.issue(a_stage(0), kt0, iw);
     lb.issue(b_stage(0), kt0, iw);
-    dg_static_for<LB2>([&](auto j_tag) { lb.template issue_one<decltype(j_tag)::value>(b_stage(1), kt0 + 1, iw, nk > 1); });
-    dg_static_for<LA2 / 2>([&](auto j_tag) { la.template issue_one<decltype(j_tag)::value>(a_stage(1), kt0 + 1, iw, nk > 1); });
-    if (nk > 1) __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LB2 + LA2 / 2)); else __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(0));
+    dg_static_for<LB_>([&](auto j_tag) { lb.template issue_one<decltype(j_tag)::value>(b_stage(1), kt0 + 1, iw, nk > 1); });
+    dg_static_for<C3>([&](auto j_tag) { la.template issue_one<decltype(j_tag)::value>(a_stage(1), kt0 + 1, iw, nk > 1); });
+    if (nk > 1) __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LB_ + C3)); else __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(0));
   } else if (issuer) {
     la.issue(smem, kt0, iw);
     lb.issue(smem + BM * DG_BK, kt0, iw);
@@ -384,7 +432,6 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
   //     barrier and the one after it, B's halves in the other two) and the path from L2 into LDS,
   //     which is what bounds a 256x256 tile, never runs dry between barriers.
   constexpr int LA = DgLoader<BM, NI, A_KMAJOR>::LPT, LB = DgLoader<BN, NI, B_KMAJOR>::LPT, LT = LPT;
-  static_assert(LS != 2 || (LA % 2 == 0 && LB % 2 == 0), "halves of each operand's loads");
   constexpr int N3 = (LT + 2) / 3, N0 = (LT - N3 + 1) / 2;
   auto kstep = [&](auto cur_tag, const bf16* ta, const bf16* tb, int ks_next, auto loads, bf16* lda_stage, int lda_kt,
                    bool lda_live, bf16* ldb_stage, int ldb_kt, bool ldb_live) {
@@ -453,9 +500,9 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
       bf16* nb = b_stage(bs1);
       bf16* nnb = b_stage(bs2);   // held tile kt-1: free since the last barrier
       const bool live1 = kt + 1 < nk, live2 = kt + 2 < nk;
-      kstep(S0{}, ca, cb, 1, DgLoads<LA / 2, LA>{}, na, kt0 + kt + 1, live1, nnb, 0, false);
-      kstep(S1{}, ca, cb, 2, DgLoads<LA, LA + LB / 2>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
-      kstep(S0{}, ca, cb, 3, DgLoads<LA + LB / 2, LT>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
+      kstep(S0{}, ca, cb, 1, DgLoads<C3, C0>{}, na, kt0 + kt + 1, live1, nnb, kt0 + kt + 2, live2);
+      kstep(S1{}, ca, cb, 2, DgLoads<C0, C1>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
+      kstep(S0{}, ca, cb, 3, DgLoads<C1, LT>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
       // tile kt+1 must have landed (A's second half went out three k-steps ago, B's a period ago); the
       // LB loads of B(kt+2) sent since then may still be in flight.  That count holds only while
       // those loads are live: past the end of the reduction they make no memory request and may
@@ -463,7 +510,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
       if (live2) __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LB) & DG_WAIT_LGKM0);
       else __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
       __builtin_amdgcn_s_barrier();
-      kstep(S1{}, na, nb, 0, DgLoads<0, LA / 2>{}, ca, kt0 + kt + 2, live2, nnb, 0, false);
+      kstep(S1{}, na, nb, 0, DgLoads<0, C3>{}, ca, kt0 + kt + 2, live2, nnb, 0, false);
       bs = bs1;
     }
   }
@@ -532,35 +579,10 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
     // time (fp32, chunk-XOR-swizzled), and re-reads it with consecutive lanes along a row,
     // so bias / residual / pre-GeLU reads and all stores are 16 bytes per lane and whole
     // 128-byte lines per row.
-    constexpr int ROWB = WN * 4;              // bytes per staged fp32 row
-    constexpr int LPR = WN / 8;               // lanes per output row (8 columns each)
-    constexpr int RPI = 64 / LPR;             // rows per store instruction
-    static_assert(NW * 32 * ROWB <= DG_STAGES * STAGE_ELEMS * 2, "epilogue staging must fit the operand stages");
+    static_assert(NW * 32 * WN * 4 <= DG_STAGES * STAGE_ELEMS * 2, "epilogue staging must fit the operand stages");
     __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
     __builtin_amdgcn_s_barrier();             // every wave is done with the operand stages
-    unsigned char* buf = dg_smem + wave * (32 * ROWB);
-    const int rrow = lane / LPR, rcol = (lane % LPR) * 8;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int c = j * 8 + g * 2 + fchunk;
-          floatx4 v = {acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
-          *reinterpret_cast<floatx4*>(buf + frow * ROWB + (((c & ~15) | ((c ^ frow) & 15)) << 4)) = v;
-        }
-      __builtin_amdgcn_s_waitcnt(DG_WAIT_LGKM0);  // own writes landed (the buffer is private to the wave)
-#pragma unroll
-      for (int sub = 0; sub < 32 / RPI; ++sub) {
-        const int r = sub * RPI + rrow, c0 = rcol / 4;
-        const floatx4 lo = *reinterpret_cast<const floatx4*>(buf + r * ROWB + (((c0 & ~15) | ((c0 ^ r) & 15)) << 4));
-        const floatx4 hi = *reinterpret_cast<const floatx4*>(buf + r * ROWB + ((((c0 + 1) & ~15) | (((c0 + 1) ^ r) & 15)) << 4));
-        float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        gemm_epilogue8<MODE>(epi, m0 + wm * WM + i * 32 + r, n0 + wn * WN + rcol, v);
-      }
-      __builtin_amdgcn_s_waitcnt(DG_WAIT_LGKM0);  // reads done before the next pass overwrites
-    }
+    dg_epilogue_bf16<MODE, TM, TN, WN>(acc, dg_smem + wave * (32 * WN * 4), epi, m0 + wm * WM, n0 + wn * WN, lane);
   }
 }
 
@@ -620,7 +642,7 @@ template <int BM, int BN, int WGM, int WGN, bool AK, bool BK_, int MODE, int LS 
 inline hipError_t dg_launch_one(const bf16* a, int64_t lda, const bf16* b, int64_t ldb, int64_t M, int64_t N,
                                 int64_t K, const EpiArgs<bf16>& epi, int splits, hipStream_t st) {
   auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, AK, BK_, MODE, LS>;
-  constexpr size_t smem = (size_t)(LS == 2 ? 2 * BM + 3 * BN : DG_STAGES * (BM + BN)) * DG_BK * sizeof(bf16);
+  constexpr size_t smem = (size_t)(LS >= 2 ? 2 * BM + 3 * BN : DG_STAGES * (BM + BN)) * DG_BK * sizeof(bf16);
   // the first call raises the kernel's dynamic LDS limit (thread-safe: initialisation of a local static)
   static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);

@@ -18,15 +18,13 @@ namespace varuna {
 //   3: both operands are the same fragments for every product;
 //   4: as 0, but 4 consecutive products add to the same accumulator tile (a dependent chain, as
 //      when the products of 4 k-steps of one output block are issued back to back);
-//   5: as 4 with chains of 2.
+//   5: as 4 with chains of 2;
+//   6: as 0 with v_mfma_f32_16x16x32_bf16, two of them per product slot (the same operations per
+//      slot; half the accumulator traffic and twice the operand traffic per operation);
+//   7: as 2 with that instruction.
 template <int PATTERN>
 __global__ __launch_bounds__(256) void mfma_rate_kernel(const bf16x8* __restrict__ src, uint32_t n_vec,
                                                         float* __restrict__ sink, int iters) {
-  floatx16 acc[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
   bf16x8 a[4], b[4];
   const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
 #pragma unroll
@@ -34,6 +32,32 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(const bf16x8* __restrict
     a[i] = src[(gid * 8u + i) % n_vec];
     b[i] = src[(gid * 8u + 4u + i) % n_vec];
   }
+  if constexpr (PATTERN >= 6) {
+    floatx4 acc4[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc4[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; it += 4) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int ia = PATTERN == 6 ? (i & 3) : u;
+          const int ib = PATTERN == 6 ? ((i + u) & 3) : ((i >> 1) & 3);
+          acc4[2 * i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ia], b[ib], acc4[2 * i], 0, 0, 0);
+          acc4[2 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ia], b[(ib + 1) & 3], acc4[2 * i + 1], 0, 0, 0);
+        }
+    }
+    float s4 = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s4 += acc4[i][0] + acc4[i][1] + acc4[i][2] + acc4[i][3];
+    sink[gid] = s4;
+    return;
+  }
+  floatx16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
   for (int it = 0; it < iters; it += 4) {
 #pragma unroll
     for (int u = 0; u < 4; ++u)

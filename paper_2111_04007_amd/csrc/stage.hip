@@ -1001,7 +1001,7 @@ varuna_status_t varuna_debug_set_gemm_kernels(int32_t fwd256, int32_t dgrad256, 
 
 varuna_status_t varuna_probe_mfma_rate(const void* operands, int64_t n_elems, int32_t waves_per_simd, int32_t pattern,
                                        int32_t iters, float* sink, double* flops, void* hip_stream) {
-  if (pattern < 0 || pattern > 5) return fail(VARUNA_EINVAL, "pattern must be in [0, 5]");
+  if (pattern < 0 || pattern > 7) return fail(VARUNA_EINVAL, "pattern must be in [0, 7]");
   if (!operands || !sink) return fail(VARUNA_EINVAL, "NULL pointer");
   if (n_elems < 8 || n_elems > (1ll << 31) || n_elems % 8 != 0) return fail(VARUNA_EINVAL, "n_elems must be a multiple of 8 in [8, 2^31]");
   if (reinterpret_cast<uintptr_t>(operands) % 16 != 0) return fail(VARUNA_EINVAL, "operands must be 16-byte aligned");
@@ -1021,7 +1021,9 @@ varuna_status_t varuna_probe_mfma_rate(const void* operands, int64_t n_elems, in
     case 2: hipLaunchKernelGGL(mfma_rate_kernel<2>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
     case 3: hipLaunchKernelGGL(mfma_rate_kernel<3>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
     case 4: hipLaunchKernelGGL(mfma_rate_kernel<4>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
-    default: hipLaunchKernelGGL(mfma_rate_kernel<5>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
+    case 5: hipLaunchKernelGGL(mfma_rate_kernel<5>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
+    case 6: hipLaunchKernelGGL(mfma_rate_kernel<6>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
+    default: hipLaunchKernelGGL(mfma_rate_kernel<7>, dim3(nwg), dim3(256), 0, s, src, nv, sink, (int)iters); break;
   }
   if (flops) *flops = (double)nwg * 4.0 * (double)iters * 8.0 * (2.0 * 32 * 32 * 16);
   return hip_result(hipGetLastError(), "varuna_probe_mfma_rate");

@@ -239,8 +239,10 @@ varuna_status_t varuna_stage_debug_saved_region(const varuna_stage_t* st, size_t
 
 /* Tuning aid: which bf16 MFMA GEMM kernel configuration (the `variant` numbers of varuna_op_gemm)
  * the stage calls use for forward / dgrad / wgrad products on 256x256 and on 128x128 tiles; 0
- * restores the library's choice.  Process-wide, not thread-safe, for same-process A/B timing
- * only: results of every configuration agree to rounding but not bit for bit. */
+ * restores the library's choice.  Naming a 128x128 configuration for forward or dgrad also turns
+ * off the library's merging of 128x128 tile pairs into one 128x256 / 256x128 tile (configurations
+ * 15 / 16) for products of 257..512 such tiles.  Process-wide, not thread-safe, for same-process
+ * A/B timing only: results of every configuration agree to rounding but not bit for bit. */
 varuna_status_t varuna_debug_set_gemm_kernels(int32_t fwd256, int32_t dgrad256, int32_t wgrad256,
                                               int32_t fwd128, int32_t dgrad128, int32_t wgrad128);
 

@@ -238,6 +238,15 @@ __device__ __forceinline__ void dg_epilogue_bf16(floatx16 (&acc)[TM][TN], unsign
   }
 }
 
+// Dynamic LDS of one workgroup: the operand stages, or the epilogue's per-wave staging where that is larger.
+template <int BM, int BN, int WGM, int WGN, int MODE, int LS>
+constexpr size_t dg_smem_bytes() {
+  const size_t stages = (size_t)(LS >= 2 ? 2 * BM + 3 * BN : DG_STAGES * (BM + BN)) * DG_BK * 2;
+  const size_t pass = (size_t)WGM * WGN * 32 * (BN / WGN) * 4;   // 32 rows x WN floats per wave
+  const size_t epi = (MODE == EPI_ACCUM_F32 || MODE == EPI_STORE_F32) ? 2 * pass : pass;
+  return stages > epi ? stages : epi;
+}
+
 // LS (load schedule): 0 = the loads of a k-tile go out in one run right after the barrier that
 // frees their stage (from the upper half of the waves, or from both halves one k-step apart,
 // see below); 1 = every wave sends its share one load at a time between its products, spread
@@ -527,7 +536,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
     constexpr int CPR = WN / 4;                 // 16-byte chunks per row of the pass block
     constexpr int PASS_BYTES = 32 * WN * 4;
     constexpr int NINS = PASS_BYTES / 1024;     // direct loads per pass
-    static_assert(NW * 2 * PASS_BYTES <= DG_STAGES * STAGE_ELEMS * 2, "epilogue staging must fit the operand stages");
+    static_assert(NW * 2 * PASS_BYTES <= dg_smem_bytes<BM, BN, WGM, WGN, MODE, LS>(), "epilogue staging must fit the workgroup's LDS");
     __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
     __builtin_amdgcn_s_barrier();               // every wave is done with the operand stages
     unsigned char* mybuf = dg_smem + wave * (2 * PASS_BYTES);
@@ -579,7 +588,7 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
     // time (fp32, chunk-XOR-swizzled), and re-reads it with consecutive lanes along a row,
     // so bias / residual / pre-GeLU reads and all stores are 16 bytes per lane and whole
     // 128-byte lines per row.
-    static_assert(NW * 32 * WN * 4 <= DG_STAGES * STAGE_ELEMS * 2, "epilogue staging must fit the operand stages");
+    static_assert(NW * 32 * WN * 4 <= dg_smem_bytes<BM, BN, WGM, WGN, MODE, LS>(), "epilogue staging must fit the workgroup's LDS");
     __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
     __builtin_amdgcn_s_barrier();             // every wave is done with the operand stages
     dg_epilogue_bf16<MODE, TM, TN, WN>(acc, dg_smem + wave * (32 * WN * 4), epi, m0 + wm * WM, n0 + wn * WN, lane);
@@ -591,12 +600,14 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
 //   5: 256x256 tile, 8 waves   6: 256x256, 4 waves   7: 128x128, 4 waves   8: 256x128, 4 waves
 //   9: as 5 with the spread load schedule   10: as 7 with the spread load schedule   11: as 6 with it
 //   12: as 5 with three stages of B and loads in every k-step   13: as 6 with that   14: as 7 with that
+//   15: 128x256, 8 waves, that schedule   16: 256x128, 8 waves, that schedule
 // ---------------------------------------------------------------------------
 inline bool dg_variant_tile(int variant, GemmTile* t) {
   switch (variant) {
     case 5: case 6: case 9: case 11: case 12: case 13: *t = {256, 256}; return true;
     case 7: case 10: case 14: *t = {128, 128}; return true;
-    case 8: *t = {256, 128}; return true;
+    case 8: case 16: *t = {256, 128}; return true;
+    case 15: *t = {128, 256}; return true;
     default: return false;
   }
 }
@@ -629,7 +640,7 @@ inline int dg_choose_variant(int64_t M, int64_t N, int64_t K, int64_t lda, int64
 // LDS reads per product) with a third B stage and loads in every k-step; dgrad keeps 8 waves
 // (two per SIMD hide each other's waits on the two-instruction transposed reads) with the same
 // load schedule; wgrad, both of whose operands are read transposed, keeps the two-stage kernel.
-struct DgFlavours { int fwd256 = 13, bwd256 = 12, fwd128 = 14, dgrad128 = 14, wgrad128 = 7, wgrad256 = 5; };
+struct DgFlavours { int fwd256 = 13, bwd256 = 12, fwd128 = 14, dgrad128 = 14, wgrad128 = 7, wgrad256 = 5; bool pair128 = true; };
 inline DgFlavours& dg_flavours() { static DgFlavours f; return f; }   // tuning hook: varuna_debug_set_gemm_kernels
 inline int dg_flavour(int tile_variant, int op) {
   const DgFlavours& f = dg_flavours();
@@ -638,11 +649,30 @@ inline int dg_flavour(int tile_variant, int op) {
   return tile_variant;
 }
 
+// The library's choice for one product.  On top of the tile size and its kernel configuration: when
+// the 128x128 tiles of a forward or dgrad product number more than the chip has CUs but no more than
+// it has slots for them (two per CU), part of the CUs would hold two tiles and the rest one.  The tiles
+// are then merged in pairs into 128x256 (else 256x128) tiles on 8 waves, one per CU: the same CUs
+// are busy for the same products, but the pair shares one operand panel through LDS, a quarter less
+// L2->LDS traffic, which is what bounds the 128x128 kernel (64 B per clock and CU).
+inline int dg_pick(int op, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb) {
+  const int tile = dg_choose_variant(M, N, K, lda, ldb);
+  if (tile == 7 && op != GEMM_WGRAD && dg_flavours().pair128) {
+    const int64_t t = (M / 128) * (N / 128);
+    if (t > 256 && t <= 512) {
+      if (dg_shape_ok(15, M, N, K, lda, ldb)) return 15;
+      if (dg_shape_ok(16, M, N, K, lda, ldb)) return 16;
+    }
+  }
+  return dg_flavour(tile, op);
+}
+
 template <int BM, int BN, int WGM, int WGN, bool AK, bool BK_, int MODE, int LS = 0>
 inline hipError_t dg_launch_one(const bf16* a, int64_t lda, const bf16* b, int64_t ldb, int64_t M, int64_t N,
                                 int64_t K, const EpiArgs<bf16>& epi, int splits, hipStream_t st) {
   auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, AK, BK_, MODE, LS>;
-  constexpr size_t smem = (size_t)(LS >= 2 ? 2 * BM + 3 * BN : DG_STAGES * (BM + BN)) * DG_BK * sizeof(bf16);
+  constexpr size_t smem = dg_smem_bytes<BM, BN, WGM, WGN, MODE, LS>();
+  static_assert(smem <= 160 * 1024, "one workgroup's LDS");
   // the first call raises the kernel's dynamic LDS limit (thread-safe: initialisation of a local static)
   static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -669,6 +699,8 @@ inline hipError_t dg_launch_variant(int variant, const bf16* a, int64_t lda, con
     case 12: return dg_launch_one<256, 256, 2, 4, AK, BK_, MODE, 2>(a, lda, b, ldb, M, N, K, epi, splits, st);
     case 13: return dg_launch_one<256, 256, 2, 2, AK, BK_, MODE, 2>(a, lda, b, ldb, M, N, K, epi, splits, st);
     case 14: return dg_launch_one<128, 128, 2, 2, AK, BK_, MODE, 2>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 15: return dg_launch_one<128, 256, 2, 4, AK, BK_, MODE, 2>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 16: return dg_launch_one<256, 128, 4, 2, AK, BK_, MODE, 2>(a, lda, b, ldb, M, N, K, epi, splits, st);
     default: return hipErrorInvalidValue;
   }
 }

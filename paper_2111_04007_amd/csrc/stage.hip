@@ -266,7 +266,7 @@ template <> struct GemmDispatch<bf16> {
                         aligned16(e.out) && aligned16(e.aux_out) && aligned16(e.out_f32) && (N % 8 == 0);
     int v = variant;
     if (v == 0) {
-      v = ptr_ok ? dg_flavour(dg_choose_variant(M, N, K, lda, ldb), op) : -1;
+      v = ptr_ok ? dg_pick(op, M, N, K, lda, ldb) : -1;
       if (v == 0) v = -1;
     }
     if (v >= 5) {
@@ -996,6 +996,7 @@ varuna_status_t varuna_debug_set_gemm_kernels(int32_t fwd256, int32_t dgrad256, 
   DgFlavours& f = dg_flavours();
   f.fwd256 = fwd256 ? fwd256 : d.fwd256; f.bwd256 = dgrad256 ? dgrad256 : d.bwd256; f.wgrad256 = wgrad256 ? wgrad256 : d.wgrad256;
   f.fwd128 = fwd128 ? fwd128 : d.fwd128; f.dgrad128 = dgrad128 ? dgrad128 : d.dgrad128; f.wgrad128 = wgrad128 ? wgrad128 : d.wgrad128;
+  f.pair128 = fwd128 == 0 && dgrad128 == 0;   // naming a 128x128 configuration also turns the merging of tile pairs off
   return VARUNA_OK;
 }
 

@@ -77,6 +77,8 @@ def test_gemm_bf16_simple_kernel(shape):
     (12, (512, 768, 256)), (12, (256, 256, 64)), (12, (256, 512, 128)), (12, (512, 256, 448)),
     (13, (512, 768, 256)), (13, (256, 256, 64)), (13, (256, 512, 192)),
     (14, (384, 640, 320)), (14, (128, 128, 64)), (14, (256, 128, 192)),
+    (15, (384, 768, 320)), (15, (128, 256, 64)), (15, (256, 512, 192)),
+    (16, (768, 384, 320)), (16, (256, 128, 64)), (16, (512, 256, 192)),
 ])
 def test_gemm_bf16_mfma_variants(variant, shape):
     """Each MFMA tile configuration on several tiles, k-steps and a single-k-step case."""
@@ -204,7 +206,7 @@ def test_attention_mfma_rejects_unsupported_shape():
     assert ei.value.code == B.EUNSUPPORTED
 
 
-@pytest.mark.parametrize("variant", [12, 13, 14, 9])
+@pytest.mark.parametrize("variant", [12, 13, 14, 9, 15, 16])
 def test_gemm_bit_stable_under_memory_contention(variant):
     """The kernels that keep loads in flight across a barrier must not let a k-tile be read
     before it has landed when memory latency rises (a wait that counted loads past the end of
@@ -246,7 +248,7 @@ def test_gemm_bit_stable_under_memory_contention(variant):
                 assert torch.equal(got, want), (variant, K)
 
 
-@pytest.mark.parametrize("variant", [5, 6, 7, 8, 9, 10, 11, 12, 13, 14])
+@pytest.mark.parametrize("variant", [5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16])
 def test_gemm_bf16_variants_to_rounding_accuracy(variant):
     """The whole-stage tolerance (2e-2) would hide a k-tile read before it landed or dropped from
     a long reduction.  Here every kernel configuration is held to what its arithmetic allows: the

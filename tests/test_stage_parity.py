@@ -196,8 +196,10 @@ def test_c5_accumulation_linearity_on_gpu():
 def test_recompute_equals_stored_bitwise():
     """The activations re-derived by backward_recompute are bit-identical to those a
     storing forward produced (same kernels, same launch geometry)."""
+    # (the third shape has products of 384 128x128 tiles, which run on merged 128x256 tiles)
     for cfg in (CONFIGS["C1"],
-                synth.StageConfig("small-bf16", 2, 256, 4, 256, 2, 2, 1024, True, "bf16", 0.02, seed=9)):
+                synth.StageConfig("small-bf16", 2, 256, 4, 256, 2, 2, 1024, True, "bf16", 0.02, seed=9),
+                synth.StageConfig("one-8.3b-layer", 1, 3072, 24, 1024, 2, 1, 12288, True, "bf16", 0.02, seed=10)):
         params = synth.make_params(cfg, perturb=0.05)
         xs, dys = synth.make_activations(cfg, 1)
         st = B.Stage(cfg)

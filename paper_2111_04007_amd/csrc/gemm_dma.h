@@ -649,19 +649,24 @@ inline int dg_flavour(int tile_variant, int op) {
   return tile_variant;
 }
 
-// The library's choice for one product.  On top of the tile size and its kernel configuration: when
-// the 128x128 tiles of a forward or dgrad product number more than the chip has CUs but no more than
-// it has slots for them (two per CU), part of the CUs would hold two tiles and the rest one.  The tiles
-// are then merged in pairs into 128x256 (else 256x128) tiles on 8 waves, one per CU: the same CUs
-// are busy for the same products, but the pair shares one operand panel through LDS, a quarter less
-// L2->LDS traffic, which is what bounds the 128x128 kernel (64 B per clock and CU).
+// The library's choice for one product.  On top of the tile size and its kernel configuration:
+// two 128x128 workgroups on a CU are bound by the CU's path from L2 (64 B per clock), so forward
+// and dgrad products may run on 128x256 (else 256x128) tiles of 8 waves instead, one per CU: a pair
+// of tiles that shares one operand panel through LDS, a quarter less L2->LDS traffic, measured 8 %
+// faster per product.  The merged tiles come in whole rounds of one per CU.  A 128x128 workgroup alone
+// on a CU runs at nearly twice the speed (0.55 of a full round's time for a product of at most 256
+// tiles), one CU holding two makes the round a full one, and beyond 512 tiles the slots refill as
+// they drain; in units of one full round of 512 tiles the two cost 0.55 / 1 / (tiles / 512) and
+// 0.92 * ceil(tiles / 2 / 256).
 inline int dg_pick(int op, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb) {
   const int tile = dg_choose_variant(M, N, K, lda, ldb);
   if (tile == 7 && op != GEMM_WGRAD && dg_flavours().pair128) {
     const int64_t t = (M / 128) * (N / 128);
-    if (t > 256 && t <= 512) {
-      if (dg_shape_ok(15, M, N, K, lda, ldb)) return 15;
-      if (dg_shape_ok(16, M, N, K, lda, ldb)) return 16;
+    const int wide = dg_shape_ok(15, M, N, K, lda, ldb) ? 15 : (dg_shape_ok(16, M, N, K, lda, ldb) ? 16 : 0);
+    if (wide != 0) {
+      const double c128 = t <= 256 ? 0.55 : (t <= 512 ? 1.0 : (double)t / 512.0);
+      const double cw = 0.92 * (double)((t / 2 + 255) / 256);
+      if (cw < c128 - 0.01) return wide;
     }
   }
   return dg_flavour(tile, op);

@@ -245,6 +245,11 @@ varuna_status_t varuna_stage_debug_saved_region(const varuna_stage_t* st, size_t
  * A/B timing only: results of every configuration agree to rounding but not bit for bit. */
 varuna_status_t varuna_debug_set_gemm_kernels(int32_t fwd256, int32_t dgrad256, int32_t wgrad256,
                                               int32_t fwd128, int32_t dgrad128, int32_t wgrad128);
+/* Host only (no GPU call): the kernel configuration the library picks for a bf16 product of
+ * contiguous, 16-byte aligned operands, op as in varuna_op_gemm (0 forward, 1 dgrad, 2 wgrad):
+ * a `variant` number of varuna_op_gemm, -1 for the plain FMA kernel (shape not a multiple of
+ * the MFMA tiles), -2 for an invalid argument. */
+int32_t varuna_debug_gemm_choice(int32_t op, int64_t M, int64_t N, int64_t K);
 
 /* ---- per-kernel timing (HIP events on the caller's stream) -------------- */
 

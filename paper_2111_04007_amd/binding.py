@@ -34,6 +34,7 @@ EXPORTS = (
     "varuna_op_colreduce_scratch_bytes", "varuna_op_attention_fwd", "varuna_op_attention_bwd",
     "varuna_op_colsum_static", "varuna_op_colsum_static_max_bytes", "varuna_probe_mfma_rate",
     "varuna_debug_set_gemm_kernels",
+    "varuna_debug_gemm_choice",
 )
 
 
@@ -104,6 +105,7 @@ def load():
         "varuna_op_colsum_static": (i32, [i32, i64, i64, vp, vp, vp]),
         "varuna_op_colsum_static_max_bytes": (sz, []),
         "varuna_debug_set_gemm_kernels": (i32, [i32] * 6),
+        "varuna_debug_gemm_choice": (i32, [i32, i64, i64, i64]),
         "varuna_probe_mfma_rate": (i32, [vp, i64, i32, i32, i32, vp, C.POINTER(C.c_double), vp]),
         "varuna_op_attention_fwd": (i32, [i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp]),
         "varuna_op_attention_bwd": (i32, [i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
@@ -306,6 +308,11 @@ def colsum_static_max_bytes() -> int:
 
 def debug_set_gemm_kernels(fwd256=0, dgrad256=0, wgrad256=0, fwd128=0, dgrad128=0, wgrad128=0):
     _check(load().varuna_debug_set_gemm_kernels(fwd256, dgrad256, wgrad256, fwd128, dgrad128, wgrad128))
+
+
+def debug_gemm_choice(op: int, M: int, N: int, K: int) -> int:
+    """Host only: the bf16 GEMM kernel configuration the library picks for this product."""
+    return int(load().varuna_debug_gemm_choice(op, M, N, K))
 
 
 def probe_mfma_rate(operands, waves_per_simd: int, iters: int, sink, pattern: int = 0, stream=None) -> float:

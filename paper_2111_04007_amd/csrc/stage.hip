@@ -1000,6 +1000,13 @@ varuna_status_t varuna_debug_set_gemm_kernels(int32_t fwd256, int32_t dgrad256, 
   return VARUNA_OK;
 }
 
+int32_t varuna_debug_gemm_choice(int32_t op, int64_t M, int64_t N, int64_t K) {
+  if (op < GEMM_FWD || op > GEMM_WGRAD || M < 1 || N < 1 || K < 1) return -2;
+  const int64_t lda = (op == GEMM_WGRAD) ? M : K, ldb = (op == GEMM_FWD) ? K : N;
+  const int v = (N % 8 == 0) ? dg_pick(op, M, N, K, lda, ldb) : 0;
+  return v == 0 ? -1 : v;
+}
+
 varuna_status_t varuna_probe_mfma_rate(const void* operands, int64_t n_elems, int32_t waves_per_simd, int32_t pattern,
                                        int32_t iters, float* sink, double* flops, void* hip_stream) {
   if (pattern < 0 || pattern > 7) return fail(VARUNA_EINVAL, "pattern must be in [0, 7]");

@@ -144,3 +144,28 @@ def test_grouped_rings_must_stay_addressable_with_32_bit_offsets():
     assert B.query_sizes(c5.replace(wgrad_group=31))[3] > 0
     _expect(B.EUNSUPPORTED, B.query_sizes, c5.replace(wgrad_group=32))
     assert B.query_sizes(CONFIGS["C1"].replace(wgrad_group=64))[3] > 0
+
+
+def test_gemm_kernel_choice_for_the_named_stage_shapes():
+    """Which bf16 GEMM configuration the library picks (host-only query): 256x256 tiles where they
+    fill the 256 CUs in whole rounds, 128x128 tiles otherwise, and merged 128x256 / 256x128 tiles
+    where two 128x128 tiles per CU would share nothing and the merged form needs no more rounds."""
+    FWD, DGRAD, WGRAD = 0, 1, 2
+    T, h, f = 2048, 8192, 32768                                    # C5: everything on 256x256 tiles
+    assert B.debug_gemm_choice(FWD, T, 3 * h, h) == 13 and B.debug_gemm_choice(FWD, T, h, f) == 13
+    assert B.debug_gemm_choice(DGRAD, T, f, h) == 12 and B.debug_gemm_choice(DGRAD, T, h, 3 * h) == 12
+    assert B.debug_gemm_choice(WGRAD, h, f, T) == 5 and B.debug_gemm_choice(WGRAD, 3 * h, h, 8 * T) == 5
+    T, h, f = 2048, 3072, 12288                                    # C4
+    assert B.debug_gemm_choice(FWD, T, 3 * h, h) == 14             # 1152 tiles: 2.25 rounds, elastic
+    assert B.debug_gemm_choice(FWD, T, h, h) == 15                 # 384 tiles -> 192 merged, one round
+    assert B.debug_gemm_choice(FWD, T, f, h) == 15                 # 1536 tiles -> 768 merged, 3 whole rounds
+    assert B.debug_gemm_choice(DGRAD, T, h, f) == 15
+    assert B.debug_gemm_choice(WGRAD, h, f, T) == 7                # weight gradients stay on 128x128
+    T, h, f = 4096, 1920, 7680                                     # C3: 1920 = 15 x 128, only M is a multiple of 256
+    assert B.debug_gemm_choice(FWD, T, h, h) == 16 and B.debug_gemm_choice(DGRAD, T, h, 3 * h) == 16
+    assert B.debug_gemm_choice(FWD, T, f, h) == 13                 # 480 256x256 tiles: two rounds beat four of 128x128
+    T, h, f = 4096, 1024, 4096                                     # C2
+    assert B.debug_gemm_choice(FWD, T, h, h) == 14                 # 256 tiles: one workgroup per CU
+    assert B.debug_gemm_choice(FWD, T, 3 * h, h) == 14             # 768 tiles: 1.5 rounds against 2 merged
+    assert B.debug_gemm_choice(FWD, 100, 128, 64) == -1            # ragged: the plain kernel
+    assert B.debug_gemm_choice(7, 128, 128, 64) == -2

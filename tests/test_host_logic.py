@@ -166,6 +166,7 @@ def test_gemm_kernel_choice_for_the_named_stage_shapes():
     assert B.debug_gemm_choice(FWD, T, f, h) == 13                 # 480 256x256 tiles: two rounds beat four of 128x128
     T, h, f = 4096, 1024, 4096                                     # C2
     assert B.debug_gemm_choice(FWD, T, h, h) == 14                 # 256 tiles: one workgroup per CU
-    assert B.debug_gemm_choice(FWD, T, 3 * h, h) == 14             # 768 tiles: 1.5 rounds against 2 merged
+    assert B.debug_gemm_choice(FWD, T, 3 * h, h) == 13             # 192 256x256 tiles: one round
+    assert B.debug_gemm_choice(DGRAD, T, h, 3 * h) == 14
     assert B.debug_gemm_choice(FWD, 100, 128, 64) == -1            # ragged: the plain kernel
     assert B.debug_gemm_choice(7, 128, 128, 64) == -2

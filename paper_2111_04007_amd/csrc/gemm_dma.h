@@ -1,7 +1,8 @@
-// bf16 MFMA GEMM for gfx950, second generation: operands go from global memory
-// straight into LDS (buffer_load_dwordx4 ... lds, no register staging) into two
-// stages of 64 k, and MFMA fragments are software-pipelined in registers across
-// k-steps and across k-tiles, with one workgroup barrier per k-tile.
+// bf16 MFMA GEMM for gfx950: operands go from global memory straight into LDS
+// (buffer_load_dwordx4 ... lds, no register staging) into stages of 64 k (two per
+// operand, or two of A and three of B: template parameter LS), and MFMA fragments
+// are software-pipelined in registers across k-steps and across k-tiles, with one
+// workgroup barrier per k-tile.
 //
 //   acc[m,n] = sum_k A(m,k) * B(n,k)
 //   A_KMAJOR: A(m,k) = a[m*lda + k]   else (m-major): A(m,k) = a[k*lda + m]

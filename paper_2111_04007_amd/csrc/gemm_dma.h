@@ -131,30 +131,58 @@ __device__ __forceinline__ void dg_settle(DgFragReg<true, true>& f) { asm volati
 __device__ __forceinline__ void dg_settle(DgFragReg<false, true>& f) {
   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.lo), "+v"(f.hi));
 }
+// The same for a whole array of fragments with one wait.
+template <int N> __device__ __forceinline__ void dg_settle_all(DgFragReg<true, false> (&)[N]) {}
+template <int N> __device__ __forceinline__ void dg_settle_all(DgFragReg<true, true> (&f)[N]) {
+  if constexpr (N == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].v), "+v"(f[1].v));
+  else if constexpr (N == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].v), "+v"(f[1].v), "+v"(f[2].v), "+v"(f[3].v));
+  else {
+#pragma unroll
+    for (int i = 0; i < N; ++i) dg_settle(f[i]);
+  }
+}
+template <int N> __device__ __forceinline__ void dg_settle_all(DgFragReg<false, true> (&f)[N]) {
+  if constexpr (N == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi));
+  else if constexpr (N == 4)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi), "+v"(f[2].lo), "+v"(f[2].hi),
+                 "+v"(f[3].lo), "+v"(f[3].hi));
+  else {
+#pragma unroll
+    for (int i = 0; i < N; ++i) dg_settle(f[i]);
+  }
+}
 
-// Fragment reader: the 8 consecutive k-values ks*16 + (lane/32)*8 .. of tile row row_base + lane%32.
+// Fragment reader: the 8 consecutive k-values KS*16 + (lane/32)*8 .. of row lane%32 of fragment number IDX
+// (32 rows each) of the wave's sub-tile, whose first row is wave_base (a multiple of 64).  Fragment number
+// and k-step are compile-time values: in the hand-issued forms whatever part of the address they contribute
+// additively goes into the instruction's offset field instead of into an address computation.
 template <int ROWS, bool KMAJOR, bool HAND>
 struct DgFrag {
-  static __device__ __forceinline__ void fetch(DgFragReg<KMAJOR, HAND>& f, const bf16* lds_tile, int row_base, int ks, int lane) {
+  template <int IDX, int KS>
+  static __device__ __forceinline__ void fetch(DgFragReg<KMAJOR, HAND>& f, const bf16* lds_tile, int wave_base,
+                                               std::integral_constant<int, IDX>, std::integral_constant<int, KS>, int lane) {
     if constexpr (KMAJOR) {
-      const int row = row_base + (lane & 31), c = ks * 2 + (lane >> 5);
+      // the swizzle depends on the fragment number through its parity only: row bits 3..5 are 4*IDX + lane bits
+      const int row = wave_base + (IDX & 1) * 32 + (lane & 31), c = KS * 2 + (lane >> 5);
       const bf16* p0 = lds_tile + row * DG_BK + ((c ^ ((row ^ (row >> 3)) & 7)) << 3);
+      constexpr int IMM = (IDX >> 1) * 64 * DG_BK * 2;   // bytes
       if constexpr (HAND) {
         const uint32_t a0 = (uint32_t)(uintptr_t)(lds_ptr_t)const_cast<bf16*>(p0);
-        asm volatile("ds_read_b128 %0, %1" : "=v"(f.v) : "v"(a0));
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f.v) : "v"(a0), "n"(IMM));
       } else {
-        f.v = *reinterpret_cast<const bf16x8*>(p0);
+        f.v = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const unsigned char*>(p0) + IMM);
       }
     } else {
       const int blk = lane >> 4, j = lane & 15;
-      const int m = row_base + (blk & 1) * 16 + 4 * (j & 3);
+      const int m = wave_base + IDX * 32 + (blk & 1) * 16 + 4 * (j & 3);
       const int kq = j >> 2;  // k-row within its group of 4 == (krow & 3)
       const int c = m >> 3, phys = c ^ dg_tr_swizzle(kq);
-      const bf16* p0 = lds_tile + (ks * 16 + (blk >> 1) * 8 + kq) * ROWS + phys * 8 + (m & 7);
+      const bf16* p0 = lds_tile + ((blk >> 1) * 8 + kq) * ROWS + phys * 8 + (m & 7);
       const uint32_t a0 = (uint32_t)(uintptr_t)(lds_ptr_t)const_cast<bf16*>(p0);
-      const uint32_t a1 = a0 + 4 * ROWS * 2;
-      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.lo) : "v"(a0));
-      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.hi) : "v"(a1));
+      constexpr int IMM0 = KS * 16 * ROWS * 2, IMM1 = IMM0 + 4 * ROWS * 2;   // bytes
+      static_assert(IMM1 < 65536, "offset field");
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.lo) : "v"(a0), "n"(IMM0));
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(a0), "n"(IMM1));
     }
   }
 };
@@ -367,10 +395,13 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
 
   DgFragReg<A_KMAJOR, HAND> fa[2][TM];
   DgFragReg<B_KMAJOR, HAND> fb[2][TN];
-#pragma unroll
-  for (int j = 0; j < TN; ++j) DgFrag<BN, B_KMAJOR, HAND>::fetch(fb[0][j], b_stage(0), wn * WN + j * 32, 0, lane);
-#pragma unroll
-  for (int i = 0; i < TM; ++i) DgFrag<BM, A_KMAJOR, HAND>::fetch(fa[0][i], a_stage(0), wm * WM + i * 32, 0, lane);
+  static_assert(WM % 64 == 0 && WN % 64 == 0, "the fragment readers take a wave's first row as a multiple of 64");
+  using KS0 = std::integral_constant<int, 0>;
+  using KS1 = std::integral_constant<int, 1>;
+  using KS2 = std::integral_constant<int, 2>;
+  using KS3 = std::integral_constant<int, 3>;
+  dg_static_for<TN>([&](auto j) { DgFrag<BN, B_KMAJOR, HAND>::fetch(fb[0][decltype(j)::value], b_stage(0), wn * WN, j, KS0{}, lane); });
+  dg_static_for<TM>([&](auto i) { DgFrag<BM, A_KMAJOR, HAND>::fetch(fa[0][decltype(i)::value], a_stage(0), wm * WM, i, KS0{}, lane); });
 
   constexpr int NMFMA = TM * TN;
   constexpr int NREAD = (A_KMAJOR ? TM : 2 * TM) + (B_KMAJOR ? TN : 2 * TN);
@@ -382,19 +413,15 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
   // One k-step of 16: multiply fragment set `cur` while set `cur^1` is fetched from
   // (tile, ks_next).  The hints pin the order MFMA, LDS read, MFMA, LDS read, ... so the
   // LDS latency hides behind the matrix pipe.
-  auto kstep = [&](auto cur_tag, const bf16* ta, int ks_next) {
+  auto kstep = [&](auto cur_tag, const bf16* ta, auto ks_next) {
     constexpr int cur = decltype(cur_tag)::value;
     const bf16* tb = ta + BM * DG_BK;
     // hand-waited fragments of set `cur` (fetched during the previous k-step) first, so the
     // wait does not cover the reads issued next
-#pragma unroll
-    for (int j = 0; j < TN; ++j) dg_settle(fb[cur][j]);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) dg_settle(fa[cur][i]);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) DgFrag<BN, B_KMAJOR, HAND>::fetch(fb[cur ^ 1][j], tb, wn * WN + j * 32, ks_next, lane);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) DgFrag<BM, A_KMAJOR, HAND>::fetch(fa[cur ^ 1][i], ta, wm * WM + i * 32, ks_next, lane);
+    dg_settle_all(fb[cur]);
+    dg_settle_all(fa[cur]);
+    dg_static_for<TN>([&](auto j) { DgFrag<BN, B_KMAJOR, HAND>::fetch(fb[cur ^ 1][decltype(j)::value], tb, wn * WN, j, ks_next, lane); });
+    dg_static_for<TM>([&](auto i) { DgFrag<BM, A_KMAJOR, HAND>::fetch(fa[cur ^ 1][decltype(i)::value], ta, wm * WM, i, ks_next, lane); });
     // hand-issued reads go out before this k-step's products, so they have the whole k-step to land
     if constexpr (HAND) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -416,20 +443,20 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
   for (int kt = 0; kt < nk; ++kt) {
     bf16* cur = smem + (kt & 1) * STAGE_ELEMS;
     bf16* nxt = smem + ((kt & 1) ^ 1) * STAGE_ELEMS;
-    kstep(S0{}, cur, 1);
+    kstep(S0{}, cur, KS1{});
     if (SPLIT && !early && kt >= 1 && kt + 1 < nk) {  // the late half's share of tile kt+1 (tiles 0, 1: sent above)
       la.issue(nxt, kt0 + kt + 1, iw);
       lb.issue(nxt + BM * DG_BK, kt0 + kt + 1, iw);
     }
-    kstep(S1{}, cur, 2);
-    kstep(S0{}, cur, 3);
+    kstep(S1{}, cur, KS2{});
+    kstep(S0{}, cur, KS3{});
     __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
     __builtin_amdgcn_s_barrier();
     if (issuer && early && kt + 2 < nk) {
       la.issue(cur, kt0 + kt + 2, iw);
       lb.issue(cur + BM * DG_BK, kt0 + kt + 2, iw);
     }
-    kstep(S1{}, nxt, 0);
+    kstep(S1{}, nxt, KS0{});
   }
   } else {
   // Loads sent one at a time between products.  A wave's LT loads of a k-tile are numbered A's
@@ -443,18 +470,16 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
   //     which is what bounds a 256x256 tile, never runs dry between barriers.
   constexpr int LA = DgLoader<BM, NI, A_KMAJOR>::LPT, LB = DgLoader<BN, NI, B_KMAJOR>::LPT, LT = LPT;
   constexpr int N3 = (LT + 2) / 3, N0 = (LT - N3 + 1) / 2;
-  auto kstep = [&](auto cur_tag, const bf16* ta, const bf16* tb, int ks_next, auto loads, bf16* lda_stage, int lda_kt,
+  auto kstep = [&](auto cur_tag, const bf16* ta, const bf16* tb, auto ks_next, auto loads, bf16* lda_stage, int lda_kt,
                    bool lda_live, bf16* ldb_stage, int ldb_kt, bool ldb_live) {
     constexpr int cur = decltype(cur_tag)::value;
     constexpr int LO = decltype(loads)::lo, HI = decltype(loads)::hi;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) dg_settle(fb[cur][j]);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) dg_settle(fa[cur][i]);
+    dg_settle_all(fb[cur]);
+    dg_settle_all(fa[cur]);
     auto fetch_one = [&](auto r_tag) {   // read number r of the next k-step's fragments: B's first, then A's
       constexpr int R = decltype(r_tag)::value;
-      if constexpr (R < TN) DgFrag<BN, B_KMAJOR, HAND>::fetch(fb[cur ^ 1][R], tb, wn * WN + R * 32, ks_next, lane);
-      else DgFrag<BM, A_KMAJOR, HAND>::fetch(fa[cur ^ 1][R - TN], ta, wm * WM + (R - TN) * 32, ks_next, lane);
+      if constexpr (R < TN) DgFrag<BN, B_KMAJOR, HAND>::fetch(fb[cur ^ 1][R], tb, wn * WN, std::integral_constant<int, R>{}, ks_next, lane);
+      else DgFrag<BM, A_KMAJOR, HAND>::fetch(fa[cur ^ 1][R - TN], ta, wm * WM, std::integral_constant<int, R - TN>{}, ks_next, lane);
     };
     if constexpr (HAND) {
       dg_static_for<TM + TN>(fetch_one);
@@ -493,35 +518,75 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
       bf16* nxtb = nxt + BM * DG_BK;
       // A load for a k-tile past the end deposits zeros into a stage nobody reads any more.
       const bool live_next = kt + 1 < nk;   // tile kt+1's remaining loads
-      kstep(S0{}, cur, curb, 1, DgLoads<N3, N3 + N0>{}, nxt, kt0 + kt + 1, live_next, nxtb, kt0 + kt + 1, live_next);
-      kstep(S1{}, cur, curb, 2, DgLoads<N3 + N0, LT>{}, nxt, kt0 + kt + 1, live_next, nxtb, kt0 + kt + 1, live_next);
-      kstep(S0{}, cur, curb, 3, DgLoads<0, 0>{}, nxt, 0, false, nxtb, 0, false);
+      kstep(S0{}, cur, curb, KS1{}, DgLoads<N3, N3 + N0>{}, nxt, kt0 + kt + 1, live_next, nxtb, kt0 + kt + 1, live_next);
+      kstep(S1{}, cur, curb, KS2{}, DgLoads<N3 + N0, LT>{}, nxt, kt0 + kt + 1, live_next, nxtb, kt0 + kt + 1, live_next);
+      kstep(S0{}, cur, curb, KS3{}, DgLoads<0, 0>{}, nxt, 0, false, nxtb, 0, false);
       __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
       __builtin_amdgcn_s_barrier();
-      kstep(S1{}, nxt, nxtb, 0, DgLoads<0, N3>{}, cur, kt0 + kt + 2, kt + 2 < nk, curb, kt0 + kt + 2, kt + 2 < nk);
+      kstep(S1{}, nxt, nxtb, KS0{}, DgLoads<0, N3>{}, cur, kt0 + kt + 2, kt + 2 < nk, curb, kt0 + kt + 2, kt + 2 < nk);
     }
   } else {
-    int bs = 0;   // B stage of tile kt (kt mod 3)
-    for (int kt = 0; kt < nk; ++kt) {
-      bf16* ca = a_stage(kt & 1);
-      bf16* na = a_stage((kt & 1) ^ 1);
-      const int bs1 = bs == 2 ? 0 : bs + 1, bs2 = bs1 == 2 ? 0 : bs1 + 1;
-      bf16* cb = b_stage(bs);
-      bf16* nb = b_stage(bs1);
-      bf16* nnb = b_stage(bs2);   // held tile kt-1: free since the last barrier
+    // One k-tile whose A stage AP (kt mod 2) and B stage BS (kt mod 3) are compile-time values.
+    auto ktile = [&](auto ap_tag, auto bs_tag, int kt) {
+      constexpr int AP = decltype(ap_tag)::value, BS = decltype(bs_tag)::value;
+      constexpr int BS1 = (BS + 1) % 3, BS2 = (BS + 2) % 3;
+      bf16* ca = a_stage(AP);
+      bf16* na = a_stage(AP ^ 1);
+      bf16* cb = b_stage(BS);
+      bf16* nb = b_stage(BS1);
+      bf16* nnb = b_stage(BS2);   // held tile kt-1: free since the last barrier
       const bool live1 = kt + 1 < nk, live2 = kt + 2 < nk;
-      kstep(S0{}, ca, cb, 1, DgLoads<C3, C0>{}, na, kt0 + kt + 1, live1, nnb, kt0 + kt + 2, live2);
-      kstep(S1{}, ca, cb, 2, DgLoads<C0, C1>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
-      kstep(S0{}, ca, cb, 3, DgLoads<C1, LT>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
-      // tile kt+1 must have landed (A's second half went out three k-steps ago, B's a period ago); the
-      // LB loads of B(kt+2) sent since then may still be in flight.  That count holds only while
-      // those loads are live: past the end of the reduction they make no memory request and may
-      // retire ahead of older loads, so the last two k-tiles wait for everything.
-      if (live2) __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LB) & DG_WAIT_LGKM0);
+      kstep(S0{}, ca, cb, KS1{}, DgLoads<C3, C0>{}, na, kt0 + kt + 1, live1, nnb, kt0 + kt + 2, live2);
+      kstep(S1{}, ca, cb, KS2{}, DgLoads<C0, C1>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
+      kstep(S0{}, ca, cb, KS3{}, DgLoads<C1, LT>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
+      if (live2) __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LB) & DG_WAIT_LGKM0);   // (see the loop below)
       else __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
       __builtin_amdgcn_s_barrier();
-      kstep(S1{}, na, nb, 0, DgLoads<0, C3>{}, ca, kt0 + kt + 2, live2, nnb, 0, false);
-      bs = bs1;
+      kstep(S1{}, na, nb, KS0{}, DgLoads<0, C3>{}, ca, kt0 + kt + 2, live2, nnb, 0, false);
+    };
+    using S2 = std::integral_constant<int, 2>;
+    if constexpr (LS == 4) {
+      // The loop unrolled over the period of the stage pair (2 x 3 k-tiles): every LDS address of a
+      // fragment read or a load's destination is then a lane-dependent register plus a constant, and
+      // the address arithmetic that otherwise follows the stage pointers around the loop (about one
+      // vector and one scalar instruction per product) is gone.
+      int kt = 0;
+      for (; kt + 6 <= nk; kt += 6) {
+        ktile(S0{}, S0{}, kt);
+        ktile(S1{}, S1{}, kt + 1);
+        ktile(S0{}, S2{}, kt + 2);
+        ktile(S1{}, S0{}, kt + 3);
+        ktile(S0{}, S1{}, kt + 4);
+        ktile(S1{}, S2{}, kt + 5);
+      }
+      if (kt < nk) { ktile(S0{}, S0{}, kt); ++kt; }
+      if (kt < nk) { ktile(S1{}, S1{}, kt); ++kt; }
+      if (kt < nk) { ktile(S0{}, S2{}, kt); ++kt; }
+      if (kt < nk) { ktile(S1{}, S0{}, kt); ++kt; }
+      if (kt < nk) { ktile(S0{}, S1{}, kt); ++kt; }
+    } else {
+      int bs = 0;   // B stage of tile kt (kt mod 3)
+      for (int kt = 0; kt < nk; ++kt) {
+        bf16* ca = a_stage(kt & 1);
+        bf16* na = a_stage((kt & 1) ^ 1);
+        const int bs1 = bs == 2 ? 0 : bs + 1, bs2 = bs1 == 2 ? 0 : bs1 + 1;
+        bf16* cb = b_stage(bs);
+        bf16* nb = b_stage(bs1);
+        bf16* nnb = b_stage(bs2);   // held tile kt-1: free since the last barrier
+        const bool live1 = kt + 1 < nk, live2 = kt + 2 < nk;
+        kstep(S0{}, ca, cb, KS1{}, DgLoads<C3, C0>{}, na, kt0 + kt + 1, live1, nnb, kt0 + kt + 2, live2);
+        kstep(S1{}, ca, cb, KS2{}, DgLoads<C0, C1>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
+        kstep(S0{}, ca, cb, KS3{}, DgLoads<C1, LT>{}, na, 0, false, nnb, kt0 + kt + 2, live2);
+        // tile kt+1 must have landed (A's second half went out three k-steps ago, B's a period ago); the
+        // LB loads of B(kt+2) sent since then may still be in flight.  That count holds only while
+        // those loads are live: past the end of the reduction they make no memory request and may
+        // retire ahead of older loads, so the last two k-tiles wait for everything.
+        if (live2) __builtin_amdgcn_s_waitcnt(DG_WAIT_VM(LB) & DG_WAIT_LGKM0);
+        else __builtin_amdgcn_s_waitcnt(DG_WAIT_VM0_LGKM0);
+        __builtin_amdgcn_s_barrier();
+        kstep(S1{}, na, nb, KS0{}, DgLoads<0, C3>{}, ca, kt0 + kt + 2, live2, nnb, 0, false);
+        bs = bs1;
+      }
     }
   }
   }
@@ -602,13 +667,15 @@ __global__ __launch_bounds__(WGM* WGN* kWave) void gemm_dma_kernel(
 //   9: as 5 with the spread load schedule   10: as 7 with the spread load schedule   11: as 6 with it
 //   12: as 5 with three stages of B and loads in every k-step   13: as 6 with that   14: as 7 with that
 //   15: 128x256, 8 waves, that schedule   16: 256x128, 8 waves, that schedule
+//   17: as 13 with the k-tile loop unrolled over the stage period   18: as 12 with that
+//   19, 20, 21: as 14, 15, 16 with that
 // ---------------------------------------------------------------------------
 inline bool dg_variant_tile(int variant, GemmTile* t) {
   switch (variant) {
-    case 5: case 6: case 9: case 11: case 12: case 13: *t = {256, 256}; return true;
-    case 7: case 10: case 14: *t = {128, 128}; return true;
-    case 8: case 16: *t = {256, 128}; return true;
-    case 15: *t = {128, 256}; return true;
+    case 5: case 6: case 9: case 11: case 12: case 13: case 17: case 18: *t = {256, 256}; return true;
+    case 7: case 10: case 14: case 19: *t = {128, 128}; return true;
+    case 8: case 16: case 21: *t = {256, 128}; return true;
+    case 15: case 20: *t = {128, 256}; return true;
     default: return false;
   }
 }
@@ -640,8 +707,10 @@ inline int dg_choose_variant(int64_t M, int64_t N, int64_t K, int64_t lda, int64
 // a kernel alone): the 256x256 forward product runs on 4 waves (128x128 per wave: a third fewer
 // LDS reads per product) with a third B stage and loads in every k-step; dgrad keeps 8 waves
 // (two per SIMD hide each other's waits on the two-instruction transposed reads) with the same
-// load schedule; wgrad, both of whose operands are read transposed, keeps the two-stage kernel.
-struct DgFlavours { int fwd256 = 13, bwd256 = 12, fwd128 = 14, dgrad128 = 14, wgrad128 = 7, wgrad256 = 5; bool pair128 = true; };
+// load schedule, and so does wgrad (both operands read transposed); all of them with the k-tile
+// loop unrolled over the stage period, which removes the address arithmetic from the loop and was
+// worth 4.4 % of the C5 step and 1.4-2.6 % of the smaller stages' in same-process A/B.
+struct DgFlavours { int fwd256 = 17, bwd256 = 18, fwd128 = 19, dgrad128 = 19, wgrad128 = 19, wgrad256 = 18; bool pair128 = true; };
 inline DgFlavours& dg_flavours() { static DgFlavours f; return f; }   // tuning hook: varuna_debug_set_gemm_kernels
 inline int dg_flavour(int tile_variant, int op) {
   const DgFlavours& f = dg_flavours();
@@ -663,7 +732,7 @@ inline int dg_pick(int op, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t
   const int tile = dg_choose_variant(M, N, K, lda, ldb);
   if (tile == 7 && op != GEMM_WGRAD && dg_flavours().pair128) {
     const int64_t t = (M / 128) * (N / 128);
-    const int wide = dg_shape_ok(15, M, N, K, lda, ldb) ? 15 : (dg_shape_ok(16, M, N, K, lda, ldb) ? 16 : 0);
+    const int wide = dg_shape_ok(20, M, N, K, lda, ldb) ? 20 : (dg_shape_ok(21, M, N, K, lda, ldb) ? 21 : 0);
     if (wide != 0) {
       const double c128 = t <= 256 ? 0.55 : (t <= 512 ? 1.0 : (double)t / 512.0);
       const double cw = 0.92 * (double)((t / 2 + 255) / 256);
@@ -707,6 +776,11 @@ inline hipError_t dg_launch_variant(int variant, const bf16* a, int64_t lda, con
     case 14: return dg_launch_one<128, 128, 2, 2, AK, BK_, MODE, 2>(a, lda, b, ldb, M, N, K, epi, splits, st);
     case 15: return dg_launch_one<128, 256, 2, 4, AK, BK_, MODE, 2>(a, lda, b, ldb, M, N, K, epi, splits, st);
     case 16: return dg_launch_one<256, 128, 4, 2, AK, BK_, MODE, 2>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 17: return dg_launch_one<256, 256, 2, 2, AK, BK_, MODE, 4>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 18: return dg_launch_one<256, 256, 2, 4, AK, BK_, MODE, 4>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 19: return dg_launch_one<128, 128, 2, 2, AK, BK_, MODE, 4>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 20: return dg_launch_one<128, 256, 2, 4, AK, BK_, MODE, 4>(a, lda, b, ldb, M, N, K, epi, splits, st);
+    case 21: return dg_launch_one<256, 128, 4, 2, AK, BK_, MODE, 4>(a, lda, b, ldb, M, N, K, epi, splits, st);
     default: return hipErrorInvalidValue;
   }
 }

@@ -152,21 +152,21 @@ def test_gemm_kernel_choice_for_the_named_stage_shapes():
     where two 128x128 tiles per CU would share nothing and the merged form needs no more rounds."""
     FWD, DGRAD, WGRAD = 0, 1, 2
     T, h, f = 2048, 8192, 32768                                    # C5: everything on 256x256 tiles
-    assert B.debug_gemm_choice(FWD, T, 3 * h, h) == 13 and B.debug_gemm_choice(FWD, T, h, f) == 13
-    assert B.debug_gemm_choice(DGRAD, T, f, h) == 12 and B.debug_gemm_choice(DGRAD, T, h, 3 * h) == 12
-    assert B.debug_gemm_choice(WGRAD, h, f, T) == 5 and B.debug_gemm_choice(WGRAD, 3 * h, h, 8 * T) == 5
+    assert B.debug_gemm_choice(FWD, T, 3 * h, h) == 17 and B.debug_gemm_choice(FWD, T, h, f) == 17
+    assert B.debug_gemm_choice(DGRAD, T, f, h) == 18 and B.debug_gemm_choice(DGRAD, T, h, 3 * h) == 18
+    assert B.debug_gemm_choice(WGRAD, h, f, T) == 18 and B.debug_gemm_choice(WGRAD, 3 * h, h, 8 * T) == 18
     T, h, f = 2048, 3072, 12288                                    # C4
-    assert B.debug_gemm_choice(FWD, T, 3 * h, h) == 14             # 1152 tiles: 2.25 rounds, elastic
-    assert B.debug_gemm_choice(FWD, T, h, h) == 15                 # 384 tiles -> 192 merged, one round
-    assert B.debug_gemm_choice(FWD, T, f, h) == 15                 # 1536 tiles -> 768 merged, 3 whole rounds
-    assert B.debug_gemm_choice(DGRAD, T, h, f) == 15
-    assert B.debug_gemm_choice(WGRAD, h, f, T) == 7                # weight gradients stay on 128x128
+    assert B.debug_gemm_choice(FWD, T, 3 * h, h) == 19             # 1152 tiles: 2.25 rounds, elastic
+    assert B.debug_gemm_choice(FWD, T, h, h) == 20                 # 384 tiles -> 192 merged, one round
+    assert B.debug_gemm_choice(FWD, T, f, h) == 20                 # 1536 tiles -> 768 merged, 3 whole rounds
+    assert B.debug_gemm_choice(DGRAD, T, h, f) == 20
+    assert B.debug_gemm_choice(WGRAD, h, f, T) == 19                # weight gradients stay on 128x128
     T, h, f = 4096, 1920, 7680                                     # C3: 1920 = 15 x 128, only M is a multiple of 256
-    assert B.debug_gemm_choice(FWD, T, h, h) == 16 and B.debug_gemm_choice(DGRAD, T, h, 3 * h) == 16
-    assert B.debug_gemm_choice(FWD, T, f, h) == 13                 # 480 256x256 tiles: two rounds beat four of 128x128
+    assert B.debug_gemm_choice(FWD, T, h, h) == 21 and B.debug_gemm_choice(DGRAD, T, h, 3 * h) == 21
+    assert B.debug_gemm_choice(FWD, T, f, h) == 17                 # 480 256x256 tiles: two rounds beat four of 128x128
     T, h, f = 4096, 1024, 4096                                     # C2
-    assert B.debug_gemm_choice(FWD, T, h, h) == 14                 # 256 tiles: one workgroup per CU
-    assert B.debug_gemm_choice(FWD, T, 3 * h, h) == 13             # 192 256x256 tiles: one round
-    assert B.debug_gemm_choice(DGRAD, T, h, 3 * h) == 14
+    assert B.debug_gemm_choice(FWD, T, h, h) == 19                 # 256 tiles: one workgroup per CU
+    assert B.debug_gemm_choice(FWD, T, 3 * h, h) == 17             # 192 256x256 tiles: one round
+    assert B.debug_gemm_choice(DGRAD, T, h, 3 * h) == 19
     assert B.debug_gemm_choice(FWD, 100, 128, 64) == -1            # ragged: the plain kernel
     assert B.debug_gemm_choice(7, 128, 128, 64) == -2

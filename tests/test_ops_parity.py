@@ -79,6 +79,11 @@ def test_gemm_bf16_simple_kernel(shape):
     (14, (384, 640, 320)), (14, (128, 128, 64)), (14, (256, 128, 192)),
     (15, (384, 768, 320)), (15, (128, 256, 64)), (15, (256, 512, 192)),
     (16, (768, 384, 320)), (16, (256, 128, 64)), (16, (512, 256, 192)),
+    (17, (512, 768, 256)), (17, (256, 256, 64)), (17, (256, 512, 448)), (17, (256, 256, 832)),
+    (18, (512, 768, 256)), (18, (256, 256, 64)), (18, (256, 512, 448)), (18, (256, 256, 832)),
+    (19, (384, 640, 320)), (19, (128, 128, 64)), (19, (256, 128, 448)), (19, (128, 256, 832)),
+    (20, (384, 768, 320)), (20, (128, 256, 64)), (20, (256, 512, 448)),
+    (21, (768, 384, 320)), (21, (256, 128, 64)), (21, (512, 256, 448)),
 ])
 def test_gemm_bf16_mfma_variants(variant, shape):
     """Each MFMA tile configuration on several tiles, k-steps and a single-k-step case."""
@@ -206,7 +211,7 @@ def test_attention_mfma_rejects_unsupported_shape():
     assert ei.value.code == B.EUNSUPPORTED
 
 
-@pytest.mark.parametrize("variant", [12, 13, 14, 9, 15, 16])
+@pytest.mark.parametrize("variant", [12, 13, 14, 9, 15, 16, 17, 18, 19, 20, 21])
 def test_gemm_bit_stable_under_memory_contention(variant):
     """The kernels that keep loads in flight across a barrier must not let a k-tile be read
     before it has landed when memory latency rises (a wait that counted loads past the end of
@@ -248,14 +253,14 @@ def test_gemm_bit_stable_under_memory_contention(variant):
                 assert torch.equal(got, want), (variant, K)
 
 
-@pytest.mark.parametrize("variant", [5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16])
+@pytest.mark.parametrize("variant", [5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21])
 def test_gemm_bf16_variants_to_rounding_accuracy(variant):
     """The whole-stage tolerance (2e-2) would hide a k-tile read before it landed or dropped from
     a long reduction.  Here every kernel configuration is held to what its arithmetic allows: the
     fp32 weight-gradient accumulator to 1e-5, bf16 outputs to the rounding of the output itself
     (rel-L2 about 2^-9 / sqrt(3) = 1.1e-3), for reductions of 1 to 16 k-tiles."""
     M, N = 512, 768
-    for K in (64, 128, 192, 256, 1024):
+    for K in (64, 128, 192, 256, 320, 384, 448, 1024):
         x = rnd((M, K), "bf16", 60 + K)
         w = rnd((N, K), "bf16", 61 + K, 0.05)
         wd = rnd((K, N), "bf16", 62 + K, 0.05)
